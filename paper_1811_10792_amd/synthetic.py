@@ -1,0 +1,113 @@
+"""Seeded synthetic workloads for the SGP step (no SGP arithmetic lives here).
+
+These stand in for the paper's ImageNet/ResNet-50 and WMT'16/Transformer runs, which only matter
+to the update path through their shapes: the node counts 4..32 of the scaling experiments and
+model-sized flat parameter vectors.  Both the GPU tests/benchmark and the CPU-oracle tests draw
+their inputs from this module so that the two sides see identical bits.
+
+Conventions: every array is float32, shape [n, d] (one row per simulated node); "N(0, s)" uses
+s as the standard deviation; a per-node quadratic f_i(x) = 0.5 * sum_e h_i[e] (x[e] - c_i[e])^2
+has gradient h_i * (z - c_i), to which per-step noise is added.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    n: int                 # simulated nodes
+    d: int                 # parameters per node
+    peers: int             # out-peers per iteration on the directed exponential graph
+    delay: int             # 0 = blocking SGP, 1 = messages arrive one iteration late
+    gamma: float
+    momentum: float        # 0 -> plain SGD step (Alg. 1), else Nesterov (Alg. 3)
+    iterations: int
+    gradient: str          # "quadratic" (depends on z) or "fresh" (drawn anew per step)
+    grad_std: float        # noise std ("quadratic") or gradient std ("fresh")
+    x_std: float           # std of the initial x
+    stats_each_step: bool = False
+    seed: int = 0
+
+
+# The five configurations of the build's baseline description, in its order.
+WORKLOADS = {
+    "c1_n4_d1k": Workload("c1_n4_d1k", 4, 1024, 1, 0, 0.1, 0.0, 200, "quadratic", 0.01, 1.0),
+    "c2_n8_d1m": Workload("c2_n8_d1m", 8, 1 << 20, 1, 0, 0.05, 0.9, 100, "quadratic", 0.1, 1.0),
+    "c3_n16_resnet50": Workload("c3_n16_resnet50", 16, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
+                                1e-3, 0.05),
+    "c4_n32_resnet50": Workload("c4_n32_resnet50", 32, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
+                                1e-3, 0.05, stats_each_step=True),
+    "c5_n16_transformer_2peer_overlap": Workload("c5_n16_transformer_2peer_overlap", 16,
+                                                 213_000_000, 2, 1, 1e-3, 0.9, 20, "fresh",
+                                                 1e-4, 0.05),
+}
+
+
+def _rng(seed: int, *stream: int) -> np.random.Generator:
+    return np.random.default_rng([int(seed), *[int(s) for s in stream]])
+
+
+def normal(shape, std: float, seed: int, *stream: int) -> np.ndarray:
+    """float32 N(0, std) array; (seed, *stream) names the draw."""
+    return (_rng(seed, *stream).standard_normal(shape, dtype=np.float32) * np.float32(std))
+
+
+def uniform(shape, lo: float, hi: float, seed: int, *stream: int) -> np.ndarray:
+    r = _rng(seed, *stream).random(shape, dtype=np.float32)
+    return (np.float32(lo) + r * np.float32(hi - lo)).astype(np.float32)
+
+
+def quadratic_problem(n: int, d: int, seed: int = 0, x_std: float = 1.0):
+    """Curvatures h ~ U[0.5, 2], centres c ~ N(0, 1) and the initial x ~ N(0, x_std)."""
+    h = uniform((n, d), 0.5, 2.0, seed, 1)
+    c = normal((n, d), 1.0, seed, 2)
+    x0 = normal((n, d), x_std, seed, 3)
+    return h, c, x0
+
+
+def step_noise(n: int, d: int, std: float, seed: int, k: int) -> np.ndarray:
+    """Noise (or, for the "fresh" workloads, the whole gradient) of iteration k."""
+    return normal((n, d), std, seed, 4, k)
+
+
+def quadratic_gradient(h: np.ndarray, c: np.ndarray, z: np.ndarray, noise: np.ndarray) -> np.ndarray:
+    """g_i = h_i * (z_i - c_i) + noise_i, each operation rounded to float32."""
+    t = (z - c).astype(np.float32)
+    t = (h * t).astype(np.float32)
+    return (t + noise).astype(np.float32)
+
+
+def quadratic_minimiser(h: np.ndarray, c: np.ndarray) -> np.ndarray:
+    """argmin of (1/n) sum_i f_i: x*[e] = sum_i h_i[e] c_i[e] / sum_i h_i[e] (float64)."""
+    h64 = h.astype(np.float64)
+    return (h64 * c.astype(np.float64)).sum(0) / h64.sum(0)
+
+
+def initial_state(wl: Workload):
+    """x^(0), w^(0) = 1, u^(0) = 0 on the host."""
+    x0 = normal((wl.n, wl.d), wl.x_std, wl.seed, 3)
+    return x0, np.ones((wl.n,), np.float32), np.zeros((wl.n, wl.d), np.float32)
+
+
+# ---- device-side generators for the model-sized workloads (torch used for memory only) -------
+
+def device_normal(n: int, ld: int, std: float, seed: int, stream: int, device="cuda"):
+    """float32 [n, ld] N(0, std) tensor drawn on the device from a seeded generator."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed((int(seed) * 1_000_003 + int(stream)) & 0x7FFFFFFFFFFFFFFF)
+    out = torch.empty((n, ld), dtype=torch.float32, device=device)
+    out.normal_(0.0, float(std), generator=gen)
+    return out
+
+
+def sample_columns(d: int, count: int, seed: int = 0, tile: int = 1024) -> np.ndarray:
+    """Sorted, distinct coordinate indices for spot checks at full size: the first and last
+    `tile` coordinates (first tile and ragged tail of any launch) plus `count` random ones."""
+    edge = np.concatenate([np.arange(0, min(tile, d)), np.arange(max(0, d - tile), d)])
+    rnd = _rng(seed, 5).integers(0, d, size=count)
+    return np.unique(np.concatenate([edge, rnd])).astype(np.int64)
