@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the SGP update on one MI355X.
+
+A "step" is one pass of the whole hot path over all n simulated nodes: peer schedule, momentum
+update, local step, PushSum mix of x and w, de-bias and (for the workloads that ask for it) the
+consensus statistics, i.e. one sgp_step call plus one sgp_consensus_stats call.  All state and a
+small rotating pool of pre-drawn gradient buffers are resident in HBM before the timed region;
+drawing gradients is not part of the step (g is an input of the method).
+
+Prints ONE JSON line: node-parameter updates per second (n*d*K / wall time of the K steps),
+the roofline of the dominant kernel (the fused step kernel, timed with HIP events on the stream
+it runs on), and the CPU oracle timed on a bounded slice of the same workload.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes_per_update(wl) -> int:
+    """HBM bytes the method itself must move per node-parameter: state read once, state written
+    once (the gather costs nothing when a work-item owns a coordinate for all nodes)."""
+    nest = wl.momentum != 0.0
+    reads = 4 * (2 + (1 if nest else 0))          # x, g, (u)
+    writes = 4 * (2 + (1 if nest else 0))         # x, z, (u)
+    if wl.delay:
+        reads += 4                                # previous messages
+        writes += 4                               # new messages
+    return reads + writes
+
+
+def read_traffic(workload_name):
+    """HBM bytes per launch of the step kernel measured with hardware counters, if a summary for
+    this workload has been committed (profiles/step_kernel_<workload>_pmc.txt)."""
+    path = os.path.join(ROOT, "profiles", "step_kernel_%s_pmc.txt" % workload_name)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """The oracle as it stands (float32 variant, dense P per coordinate, plus the float64
+    statistics when the workload reports them), timed on the host cores on a contiguous
+    coordinate slice of the workload; coordinates are independent, so the slice is exact."""
+    import numpy as np
+    from oracle import sgp_oracle as O
+    from paper_1811_10792_amd import synthetic as syn
+    cores = len(os.sched_getaffinity(0))
+    threads = max(1, min(cores, O.max_threads()))
+    O.set_threads(threads)
+    n = wl.n
+    dslice = min(wl.d, 1 << 21)
+    x = syn.normal((n, dslice), wl.x_std, wl.seed, 3)
+    u = np.zeros((n, dslice), np.float32)
+    w = np.ones(n, np.float32)
+    g = syn.normal((n, dslice), wl.grad_std, wl.seed, 4, 0)
+    st = O.Delay1State(n, dslice, np.float32) if wl.delay else None
+    nest = wl.momentum != 0.0
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        P = O.mixing_matrix(n, wl.peers, steps, np.float32)
+        if wl.delay:
+            z = O.step_delay1(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, st, nesterov=nest)
+        else:
+            z = O.step(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, nesterov=nest)
+        if wl.stats_each_step:
+            O.consensus_stats(z, w)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or steps >= 50:
+            break
+    return {"value": n * dslice * steps / el, "unit": "node-param updates/s", "cores": threads,
+            "kind": "oracle",
+            "sample": "%d steps of %s on a contiguous slice of %d of its %d coordinates per node, "
+                      "all %d nodes, %.1f s" % (steps, wl.name, dslice, wl.d, n, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4_n32_resnet50")
+    ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all simulated nodes live in one HBM); "
+                 "--gpus %d is not supported" % args.gpus)
+
+    import torch
+    import paper_1811_10792_amd as sgp
+    from paper_1811_10792_amd import synthetic as syn
+
+    wl = syn.WORKLOADS[args.workload]
+    n, d = wl.n, wl.d
+    torch.cuda.set_device(0)
+    nest = wl.momentum != 0.0
+    eng = sgp.SGP(n, d, peers=wl.peers, delay=wl.delay)
+    X = syn.device_normal(n, d, wl.x_std, wl.seed, 3)
+    U = torch.zeros_like(X)
+    W = torch.ones(n, dtype=torch.float32, device="cuda")
+    Z = torch.empty_like(X)
+    pool = [syn.device_normal(n, d, wl.grad_std, wl.seed, 100 + i) for i in range(max(1, args.pool))]
+    do_stats = wl.stats_each_step and not args.no_stats
+    stream = torch.cuda.current_stream()
+
+    k = 0
+    last = None
+
+    def one_step(k, ev=None):
+        if ev:
+            ev[0].record(stream)
+        eng.step(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
+        if ev:
+            ev[1].record(stream)
+        return eng.consensus_stats(Z, W) if do_stats else None
+
+    for _ in range(args.warmup):
+        last = one_step(k)
+        k += 1
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        last = one_step(k, events[i])
+        k += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    kern_ms = [a.elapsed_time(b) for a, b in events]
+    avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
+    bpu = algorithmic_bytes_per_update(wl)
+    achieved = bpu * n * d / avg_kern_s / 1e9
+    out = {
+        "metric": "SGP node-param updates/sec (n*d/step time)",
+        "value": n * d * args.steps / elapsed,
+        "unit": "node-param updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n": n, "d": d, "peers": wl.peers, "delay": wl.delay,
+                   "momentum": wl.momentum, "gamma": wl.gamma,
+                   "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool)},
+        "roofline": {"bound": "hbm", "kernel": "fused sgp_step kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
+                     "algorithmic_bytes_per_update": bpu,
+                     "kernel_ms_avg": avg_kern_s * 1e3, "kernel_ms_min": min(kern_ms)},
+    }
+    if last is not None:
+        out["consensus_dist_max_last"] = last.dist_max
+    eng.close()
+    del X, U, Z, pool
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

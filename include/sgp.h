@@ -1,0 +1,160 @@
+/*
+ * sgp.h -- C ABI of the MI355X (gfx950) library for the per-iteration update of Stochastic
+ * Gradient Push (SGP, arXiv 1811.10792) over n simulated nodes whose states all live in one
+ * GPU's memory.
+ *
+ * One iteration at node i (Alg. 1; with Nesterov momentum, Alg. 3):
+ *     u_i  <- momentum * u_i + g_i                                  (Alg. 3 only)
+ *     xh_i  = x_i - gamma * (momentum * u_i + g_i)                  (Alg. 1: x_i - gamma * g_i)
+ *     x_i  <- sum_j p_ij^(k) xh_j ,   w_i <- sum_j p_ij^(k) w_j     (PushSum mix)
+ *     z_i   = x_i / w_i                                             (de-bias)
+ * with P^(k) the column-stochastic mixing matrix of the time-varying directed exponential
+ * graph with uniform weights (Appendix A "Definition of P^(k)", Appendix C).  The exchange of
+ * messages between nodes is an on-device gather; no inter-GPU communication is involved.
+ *
+ * Data layout (all device memory is CALLER-OWNED, float32):
+ *     x, m (the paper's momentum buffer u), g, z : [n][ld] row-major, one row per node, row
+ *         stride ld >= d elements; only the first d elements of a row are read or written.
+ *     w : [n].
+ * The fast path needs ld % 4 == 0 and 16-byte aligned base pointers (128-bit accesses);
+ * otherwise a scalar path is used.  Arithmetic is IEEE binary32, round to nearest even, every
+ * operation rounded separately (no fused multiply-add), correctly rounded division, subnormals
+ * kept.  Sums over senders are taken in ascending sender index.
+ *
+ * Every function returns an int status: SGP_OK or a negative SGP_ERR_* code; nothing throws or
+ * aborts.  Device work is enqueued on the given HIP stream (hipStream_t passed as void*, NULL =
+ * default stream) and is asynchronous with respect to the host unless stated otherwise.  A
+ * handle must not be used from two host threads at once, and all calls on one handle must be
+ * enqueued on streams that are ordered with respect to each other.
+ */
+#ifndef SGP_H_
+#define SGP_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SGP_OK 0
+#define SGP_ERR_INVALID_ARG (-1) /* null pointer, size or parameter out of range */
+#define SGP_ERR_UNSUPPORTED (-2) /* valid request the library has no kernel for */
+#define SGP_ERR_ALIGNMENT (-3)   /* a float pointer that is not 4-byte aligned */
+#define SGP_ERR_SEQUENCE (-4)    /* overlap mode: k is not the previous call's k plus one */
+#define SGP_ERR_HIP (-5)         /* a HIP call failed; see sgp_last_hip_error */
+#define SGP_ERR_NOMEM (-6)       /* host or device allocation failed */
+
+#define SGP_TOPO_DIRECTED_EXP 0 /* time-varying directed exponential graph (Appendix A) */
+
+#define SGP_MAX_NODES 1024 /* largest n accepted by sgp_create */
+#define SGP_MAX_PEERS 16   /* largest peers accepted by sgp_create */
+
+typedef struct sgp_handle sgp_handle;
+
+/* Result of sgp_consensus_stats ("Parameter deviations": Euclidean distance between each node's
+ * parameters and the node-wise average, summarised by mean, max and min over nodes). */
+typedef struct sgp_stats {
+    double dist_max;  /* max_i || z_i - zbar ||_2 ,  zbar = (1/n) sum_i z_i */
+    double dist_mean; /* (1/n) sum_i || z_i - zbar ||_2 */
+    double dist_min;  /* min_i || z_i - zbar ||_2 */
+    double w_sum;     /* sum_i w_i (equals n, minus weight in transit in overlap mode) */
+    double zbar_norm; /* || zbar ||_2 */
+    int32_t argmax;   /* node attaining dist_max (lowest index on ties) */
+    int32_t argmin;   /* node attaining dist_min (lowest index on ties) */
+} sgp_stats;
+
+/*
+ * Creates a handle for n nodes of d parameters with row stride ld (elements).
+ *   topology : SGP_TOPO_DIRECTED_EXP.
+ *   peers    : out-peers per iteration, 1..SGP_MAX_PEERS (the paper uses 1 and 2).  At iteration
+ *              k a node sends to the peers 2^((k+r) mod L) hops ahead, r = 0..peers-1, where
+ *              L = floor(log2(n-1)) + 1 is the length of the peer list 2^0 .. 2^floor(log2(n-1));
+ *              a peer reached twice counts once, and each out-neighbour (the node itself
+ *              included) gets weight 1/|N_out|.
+ *   delay    : 0 = blocking SGP (Alg. 1/3); 1 = 1-overlap SGP (Alg. 2 with tau = 1): the mix at
+ *              iteration k uses the node's own share of iteration k and the messages that were
+ *              sent at iteration k-1.  The library then owns two [n][ld] message buffers.
+ * Host-only: no device memory is touched until the first call that launches work.
+ * Errors: SGP_ERR_INVALID_ARG (out == NULL, n < 1, n > SGP_MAX_NODES, d < 1, ld < d, peers or
+ * delay out of range), SGP_ERR_UNSUPPORTED (unknown topology); *out is NULL on error.
+ */
+int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topology,
+               int32_t peers, int32_t delay);
+
+/* Frees the handle and the device memory the library allocated for it (never caller memory).
+ * Synchronises the device first.  NULL is accepted. */
+int sgp_destroy(sgp_handle *h);
+
+/* Overlap mode: drops the messages in flight, so that the next sgp_step receives nothing (as
+ * the first iteration of Alg. 2 does) and may start at any k.  No-op for delay == 0. */
+int sgp_reset(sgp_handle *h);
+
+/*
+ * One SGP iteration k for all nodes (Alg. 1 lines 4-8 / Alg. 3 lines 4-9; overlap mode: Alg. 2
+ * with tau = 1), in place.
+ *   x        [n][ld] device, in/out : push-sum numerators x^(k) -> x^(k+1)
+ *   w        [n]     device, in/out : push-sum weights   w^(k) -> w^(k+1)
+ *   m        [n][ld] device, in/out : momentum buffers u^(k) -> u^(k+1); may be NULL when
+ *                                     momentum == 0 (then Alg. 1 is run and m is not touched)
+ *   g        [n][ld] device, in     : stochastic gradients evaluated by the caller at z^(k)
+ *   z_out    [n][ld] device, out    : de-biased z^(k+1) = x^(k+1)/w^(k+1); NULL = not wanted;
+ *                                     must not overlap x, m or g
+ *   gamma, momentum : step size and Nesterov coefficient
+ *   k        >= 0   : iteration index; selects P^(k) (the schedule is a pure function of k)
+ * Overlap mode: the first call after sgp_create/sgp_reset receives nothing; every later call
+ * must pass the previous k plus one (else SGP_ERR_SEQUENCE and nothing is launched).  Messages
+ * sent at the last iteration stay in the library's buffers.
+ * Errors: SGP_ERR_INVALID_ARG, SGP_ERR_ALIGNMENT, SGP_ERR_SEQUENCE, SGP_ERR_UNSUPPORTED (more
+ * than one peer without delay and n > 256), SGP_ERR_NOMEM, SGP_ERR_HIP.
+ */
+int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+             float gamma, float momentum, int64_t k, void *stream);
+
+/* z_i = x_i / w_i for all nodes (last line of Alg. 1); x [n][ld], w [n], z [n][ld] device.
+ * Used for z^(0) and whenever sgp_step was called with z_out == NULL. */
+int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *stream);
+
+/*
+ * Consensus statistics of z [n][ld] (device) and w [n] (device): per-node distance to the
+ * node-wise average and its max / mean / min, sum of weights, norm of the average.
+ *   host_out           : host, written on return
+ *   per_node_dist_host : host [n] doubles, or NULL
+ * Enqueues the reduction kernels on `stream`, copies the result back and SYNCHRONISES the
+ * stream before returning.
+ */
+int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
+                        double *per_node_dist_host, void *stream);
+
+/*
+ * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).
+ *   out_peers [n][peers] : out_peers[i*peers + r] = node that i sends to over its r-th hop,
+ *                          (i + 2^((k+r) mod L)) mod n, or -1 if that peer repeats an earlier one
+ *                          (or n == 1)
+ *   in_peers  [n][peers] : in_peers[i*peers + r] = node that i receives from over the r-th hop,
+ *                          (i - 2^((k+r) mod L)) mod n, or -1 likewise
+ *   weight               : the uniform mixing weight 1/|N_out| of that iteration
+ * Any output pointer may be NULL.  In overlap mode the messages RECEIVED at iteration k are
+ * those of sgp_peer_schedule(k-1).
+ */
+int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_t *in_peers,
+                      float *weight);
+
+/* Same as sgp_peer_schedule without a handle. */
+int sgp_schedule(int32_t n, int32_t peers, int64_t k, int32_t *out_peers, int32_t *in_peers,
+                 float *weight);
+
+/* Static, human-readable name of a status code. */
+const char *sgp_status_string(int status);
+
+/* hipError_t value of the last failed HIP call on this handle (0 if none). */
+int sgp_last_hip_error(const sgp_handle *h);
+
+/* Measurement utility: plain 128-bit streaming copy of nbytes (multiple of 16, both pointers
+ * 16-byte aligned, device memory) on `stream`.  Serves as the known-size reference when
+ * hardware traffic counters are scaled, and as the practical bandwidth ceiling of the part. */
+int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGP_H_ */

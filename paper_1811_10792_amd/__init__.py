@@ -1,0 +1,9 @@
+"""MI355X-native Stochastic Gradient Push update (arXiv 1811.10792).
+
+csrc/sgp.hip holds the HIP kernels and the C ABI of include/sgp.h; binding.py marshals
+arguments; synthetic.py draws the seeded benchmark inputs.  Importing the package loads nothing;
+the HIP library is loaded on first use and its absence is an error.
+"""
+from .binding import SGP, SgpError, Stats, load_library, sgp_copy, sgp_schedule, status_string  # noqa: F401
+
+__all__ = ["SGP", "SgpError", "Stats", "load_library", "sgp_copy", "sgp_schedule", "status_string"]

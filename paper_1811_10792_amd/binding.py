@@ -1,0 +1,202 @@
+"""Thin ctypes binding of the C ABI in include/sgp.h: argument marshalling only.
+
+PyTorch appears here for device memory and streams (tensor.data_ptr(), the current stream's
+handle); every arithmetic step runs in the HIP library.  There is no fallback: if the library has
+not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsgp_hip.so")
+
+SGP_OK = 0
+SGP_ERR_INVALID_ARG = -1
+SGP_ERR_UNSUPPORTED = -2
+SGP_ERR_ALIGNMENT = -3
+SGP_ERR_SEQUENCE = -4
+SGP_ERR_HIP = -5
+SGP_ERR_NOMEM = -6
+SGP_TOPO_DIRECTED_EXP = 0
+
+# every symbol include/sgp.h declares
+EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
+           "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
+           "sgp_last_hip_error", "sgp_copy")
+
+
+class SgpError(RuntimeError):
+    def __init__(self, status: int, name: str, where: str):
+        super().__init__("%s failed: %s (%d)" % (where, name, status))
+        self.status = status
+
+
+class _CStats(ctypes.Structure):
+    _fields_ = [("dist_max", ctypes.c_double), ("dist_mean", ctypes.c_double),
+                ("dist_min", ctypes.c_double), ("w_sum", ctypes.c_double),
+                ("zbar_norm", ctypes.c_double), ("argmax", ctypes.c_int32),
+                ("argmin", ctypes.c_int32)]
+
+
+@dataclass
+class Stats:
+    dist_max: float
+    dist_mean: float
+    dist_min: float
+    w_sum: float
+    zbar_norm: float
+    argmax: int
+    argmin: int
+    per_node: Optional[list] = None
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libsgp_hip.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "HIP library %s is missing: build it first (python -m paper_1811_10792_amd.build); "
+            "there is no CPU fallback" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    lib.sgp_create.argtypes = [ctypes.POINTER(vp), i32, i64, i64, i32, i32, i32]
+    lib.sgp_destroy.argtypes = [vp]
+    lib.sgp_reset.argtypes = [vp]
+    lib.sgp_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, vp]
+    lib.sgp_debias.argtypes = [vp, vp, vp, vp, vp]
+    lib.sgp_consensus_stats.argtypes = [vp, vp, vp, ctypes.POINTER(_CStats), vp, vp]
+    lib.sgp_peer_schedule.argtypes = [vp, i64, vp, vp, ctypes.POINTER(f32)]
+    lib.sgp_schedule.argtypes = [i32, i32, i64, vp, vp, ctypes.POINTER(f32)]
+    lib.sgp_status_string.argtypes = [ctypes.c_int]
+    lib.sgp_status_string.restype = ctypes.c_char_p
+    lib.sgp_last_hip_error.argtypes = [vp]
+    lib.sgp_copy.argtypes = [vp, vp, i64, vp]
+    for name in EXPORTS:
+        if name != "sgp_status_string":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().sgp_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != SGP_OK:
+        raise SgpError(status, status_string(status), where)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (or None)."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t of a torch stream; None -> torch's current stream."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def sgp_schedule(n: int, peers: int, k: int):
+    """Handle-free peer schedule: (out_peers[n][peers], in_peers[n][peers], weight)."""
+    lib = load_library()
+    out = (ctypes.c_int32 * (n * peers))()
+    inp = (ctypes.c_int32 * (n * peers))()
+    wt = ctypes.c_float()
+    _check(lib.sgp_schedule(n, peers, k, ctypes.addressof(out), ctypes.addressof(inp),
+                            ctypes.byref(wt)), "sgp_schedule")
+    rows = lambda a: [list(a[i * peers:(i + 1) * peers]) for i in range(n)]
+    return rows(out), rows(inp), wt.value
+
+
+def sgp_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
+    if nbytes is None:
+        nbytes = src.numel() * src.element_size()
+    _check(load_library().sgp_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sgp_copy")
+
+
+class SGP:
+    """Owner of one sgp_handle.  Tensors are float32 CUDA tensors of shape [n, ld] / [n]."""
+
+    def __init__(self, n: int, d: int, ld: Optional[int] = None, topology: int = SGP_TOPO_DIRECTED_EXP,
+                 peers: int = 1, delay: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.n, self.d, self.ld = n, d, d if ld is None else ld
+        self.peers, self.delay = peers, delay
+        _check(self._lib.sgp_create(ctypes.byref(self._h), n, d, self.ld, topology, peers, delay),
+               "sgp_create")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.sgp_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _expect(self, t, name, rows_only=False):
+        if t is None:
+            return
+        if not t.is_cuda or t.dtype.is_floating_point is False or t.element_size() != 4 \
+                or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous float32 CUDA tensor" % name)
+        want = self.n if rows_only else self.n * self.ld
+        if t.numel() != want:
+            raise ValueError("%s has %d elements, expected %d" % (name, t.numel(), want))
+
+    def step(self, x, w, m, g, z_out, gamma: float, momentum: float, k: int, stream=None) -> None:
+        for t, name in ((x, "x"), (m, "m"), (g, "g"), (z_out, "z_out")):
+            self._expect(t, name)
+        self._expect(w, "w", rows_only=True)
+        _check(self._lib.sgp_step(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), _ptr(z_out),
+                                  gamma, momentum, k, _stream(stream)), "sgp_step")
+
+    def debias(self, x, w, z, stream=None) -> None:
+        self._expect(x, "x")
+        self._expect(z, "z")
+        self._expect(w, "w", rows_only=True)
+        _check(self._lib.sgp_debias(self._h, _ptr(x), _ptr(w), _ptr(z), _stream(stream)),
+               "sgp_debias")
+
+    def consensus_stats(self, z, w, per_node: bool = False, stream=None) -> Stats:
+        self._expect(z, "z")
+        self._expect(w, "w", rows_only=True)
+        cs = _CStats()
+        buf = (ctypes.c_double * self.n)() if per_node else None
+        _check(self._lib.sgp_consensus_stats(self._h, _ptr(z), _ptr(w), ctypes.byref(cs),
+                                             ctypes.addressof(buf) if per_node else None,
+                                             _stream(stream)), "sgp_consensus_stats")
+        return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
+                     cs.argmin, list(buf) if per_node else None)
+
+    def peer_schedule(self, k: int):
+        n, peers = self.n, self.peers
+        out = (ctypes.c_int32 * (n * peers))()
+        inp = (ctypes.c_int32 * (n * peers))()
+        wt = ctypes.c_float()
+        _check(self._lib.sgp_peer_schedule(self._h, k, ctypes.addressof(out), ctypes.addressof(inp),
+                                           ctypes.byref(wt)), "sgp_peer_schedule")
+        rows = lambda a: [list(a[i * peers:(i + 1) * peers]) for i in range(n)]
+        return rows(out), rows(inp), wt.value
+
+    def reset(self) -> None:
+        _check(self._lib.sgp_reset(self._h), "sgp_reset")
+
+    def last_hip_error(self) -> int:
+        return int(self._lib.sgp_last_hip_error(self._h))

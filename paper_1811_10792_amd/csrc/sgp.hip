@@ -1,0 +1,980 @@
+// SGP update for n simulated nodes resident in one MI355X's HBM: host-side peer scheduler, HIP
+// kernels for gfx950 and the C ABI declared in include/sgp.h.
+//
+// Kernel design.  The PushSum mix couples nodes but never coordinates (x <- P x acts on the
+// n-vector of one coordinate), so a work-item owns a 128-bit group of four coordinates for ALL
+// n nodes.  It reads x, u, g of every node once, writes u, x, z once, and the "messages" of
+// Alg. 1 line 5 never leave registers (or LDS): 24 bytes of HBM traffic per node-parameter, the
+// algorithmic minimum, and the in-place update is race-free because no other work-item touches
+// those coordinates.  Everything is a stream (about 0.4 flop per byte), so there is no MFMA
+// here; what matters is 128-bit coalesced accesses and enough loads in flight per CU.
+//
+// All floating-point code in this file is compiled without multiply-add contraction, so each
+// operation rounds separately, in the order written.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "sgp.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Peer scheduler (host, integers only).  Appendix A: the peer list holds the hop distances
+// 2^0 .. 2^floor(log2(n-1)), L = floor(log2(n-1)) + 1 entries; at iteration k a node sends to
+// `peers` consecutive entries starting at entry k mod L (wrapping), i.e. to (i + hop) mod n.
+// ------------------------------------------------------------------------------------------
+struct Schedule {
+    int L;                        // entries in the peer list (0 when n == 1)
+    int distinct;                 // distinct hop distances used at this iteration
+    int hop[SGP_MAX_PEERS];       // hop per requested peer slot, -1 where it repeats an earlier one
+    int uniq[SGP_MAX_PEERS];      // the distinct hops, in slot order
+    float p;                      // uniform weight 1 / (1 + distinct)
+};
+
+int peer_list_length(int n)
+{
+    int L = 0;
+    for (int t = n - 1; t > 0; t >>= 1) ++L;   // bit length of n-1
+    return L;
+}
+
+Schedule make_schedule(int n, int peers, int64_t k)
+{
+    Schedule s;
+    s.L = peer_list_length(n);
+    s.distinct = 0;
+    for (int r = 0; r < peers; ++r) {
+        s.hop[r] = -1;
+        if (s.L == 0) continue;
+        int hop = 1 << (int)((k + r) % s.L);
+        bool seen = false;
+        for (int q = 0; q < s.distinct; ++q) seen = seen || (s.uniq[q] == hop);
+        if (!seen) {
+            s.hop[r] = hop;
+            s.uniq[s.distinct++] = hop;
+        }
+    }
+    s.p = 1.0f / (float)(1 + s.distinct);
+    return s;
+}
+
+int gcd_int(int a, int b)
+{
+    while (b) { int t = a % b; a = b; b = t; }
+    return a;
+}
+
+// ------------------------------------------------------------------------------------------
+// Device helpers
+// ------------------------------------------------------------------------------------------
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <int V> struct vec_of;
+template <> struct vec_of<4> { typedef floatx4 type; };
+template <> struct vec_of<1> { typedef float type; };
+
+// The state arrays are 13-110 GB per step and are touched once: stream them past the caches.
+template <int V>
+__device__ __forceinline__ typename vec_of<V>::type ld_stream(const float *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const typename vec_of<V>::type *>(p));
+}
+template <int V>
+__device__ __forceinline__ void st_stream(float *p, typename vec_of<V>::type v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<typename vec_of<V>::type *>(p));
+}
+template <int V>
+__device__ __forceinline__ typename vec_of<V>::type ld_cached(const float *p)
+{
+    return *reinterpret_cast<const typename vec_of<V>::type *>(p);
+}
+
+__device__ __forceinline__ float hsum(floatx4 v) { return (v.x + v.y) + (v.z + v.w); }
+__device__ __forceinline__ float hsum(float v) { return v; }
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+    return v;
+}
+
+// Local optimiser step on the numerator.  Alg. 3 lines 4-5: u <- m u + g; xh = x - gamma (m u + g)
+// with the NEW u.  Alg. 1 line 4: xh = x - gamma g.
+template <int V, bool NEST>
+__device__ __forceinline__ typename vec_of<V>::type half_step(typename vec_of<V>::type xv,
+                                                             typename vec_of<V>::type uv,
+                                                             typename vec_of<V>::type gv,
+                                                             float gamma, float mom, float *u_dst)
+{
+    typedef typename vec_of<V>::type T;
+    if (NEST) {
+        T mu = mom * uv;
+        T un = mu + gv;
+        st_stream<V>(u_dst, un);
+        T mun = mom * un;
+        T dir = mun + gv;
+        T stp = gamma * dir;
+        return xv - stp;
+    } else {
+        T stp = gamma * gv;
+        return xv - stp;
+    }
+}
+
+// z = x / w, IEEE division; w == 1 (every non-delayed regular graph) needs no division at all,
+// and x / 1 == x bit for bit.
+template <int V>
+__device__ __forceinline__ typename vec_of<V>::type debias_val(typename vec_of<V>::type xn, float wi)
+{
+    return wi == 1.0f ? xn : xn / wi;
+}
+
+constexpr int kBlock = 256;     // work-items per block of the streaming kernels
+constexpr int kGatherBlock = 64;
+constexpr int kBatch = 4;       // nodes whose loads are issued back to back before any use
+
+// ------------------------------------------------------------------------------------------
+// Fused step, one out-peer (or none, n == 1).  The in-neighbour of node i is (i - h) mod n, so
+// walking a cycle c, c+h, c+2h, ... of the shift needs only the previous and the first xh of the
+// cycle in registers, for any n and any run-time h.  There are gcd(n, h) cycles of n/gcd nodes.
+//   x_new[i] = p*xh[i] + p*xh[(i-h) mod n]   (two exactly-rounded products; their sum does not
+//                                             depend on the order of the two terms)
+// ------------------------------------------------------------------------------------------
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kBlock) void k_step_one_peer(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
+    long ncols, int h, int ncyc, int len, float p, float gamma, float mom)
+{
+    typedef typename vec_of<V>::type T;
+    long c = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= ncols) return;
+    const size_t off = col0 + (size_t)c * V;
+
+    for (int cyc = 0; cyc < ncyc; ++cyc) {
+        int node = cyc;
+        T first = T(0), prev = T(0);
+        for (int t0 = 0; t0 < len; t0 += kBatch) {
+            T xv[kBatch], uv[kBatch], gv[kBatch];
+            int nd[kBatch];
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                nd[q] = node;
+                if (t0 + q < len) {
+                    size_t a = (size_t)node * ld + off;
+                    xv[q] = ld_stream<V>(x + a);
+                    if (NEST) uv[q] = ld_stream<V>(u + a);
+                    gv[q] = ld_stream<V>(g + a);
+                    node += h;
+                    if (node >= n) node -= n;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kBatch; ++q) {
+                if (t0 + q < len) {
+                    size_t a = (size_t)nd[q] * ld + off;
+                    T xh = half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
+                    if (t0 + q == 0) {
+                        first = xh;
+                    } else {
+                        T a0 = p * xh;
+                        T a1 = p * prev;
+                        T xn = a0 + a1;
+                        st_stream<V>(x + a, xn);
+                        if (ZOUT) st_stream<V>(z + a, debias_val<V>(xn, w[nd[q]]));
+                    }
+                    prev = xh;
+                }
+            }
+        }
+        // close the cycle: its first node hears from the last one visited
+        size_t a = (size_t)cyc * ld + off;
+        T xn = p * first;
+        if (len > 1) {
+            T a1 = p * prev;
+            xn = xn + a1;
+        }
+        st_stream<V>(x + a, xn);
+        if (ZOUT) st_stream<V>(z + a, debias_val<V>(xn, w[cyc]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused step, any number of out-peers: every xh of the work-item's coordinates is parked in a
+// private LDS column (no barrier: a work-item only reads what it wrote), then each receiver sums
+// its sources.  tab[i*S + q], q < S, lists node i's sources (itself included) in ascending index.
+// ------------------------------------------------------------------------------------------
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kGatherBlock) void k_step_gather(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
+    long ncols, const int *__restrict__ tab, int S, float p, float gamma, float mom)
+{
+    typedef typename vec_of<V>::type T;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *stash = reinterpret_cast<T *>(smem) + threadIdx.x;   // node i lives at stash[i * kGatherBlock]
+    long c = (long)blockIdx.x * kGatherBlock + threadIdx.x;
+    if (c >= ncols) return;
+    const size_t off = col0 + (size_t)c * V;
+
+    for (int i0 = 0; i0 < n; i0 += kBatch) {
+        T xv[kBatch], uv[kBatch], gv[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (i0 + q < n) {
+                size_t a = (size_t)(i0 + q) * ld + off;
+                xv[q] = ld_stream<V>(x + a);
+                if (NEST) uv[q] = ld_stream<V>(u + a);
+                gv[q] = ld_stream<V>(g + a);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (i0 + q < n) {
+                size_t a = (size_t)(i0 + q) * ld + off;
+                stash[(i0 + q) * kGatherBlock] =
+                    half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
+            }
+        }
+    }
+    for (int i = 0; i < n; ++i) {
+        const int *src = tab + (size_t)i * S;
+        T acc = p * stash[src[0] * kGatherBlock];
+        for (int q = 1; q < S; ++q) {
+            T term = p * stash[src[q] * kGatherBlock];
+            acc = acc + term;
+        }
+        size_t a = (size_t)i * ld + off;
+        st_stream<V>(x + a, acc);
+        if (ZOUT) st_stream<V>(z + a, debias_val<V>(acc, w[i]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused step of 1-overlap SGP (Alg. 2, tau = 1).  Node i keeps its own share p*xh_i (which is
+// also the message it sends: uniform weights), and then adds the messages that its in-neighbours
+// of the PREVIOUS iteration sent, in ascending sender index.  msg_prev/msg_cur are [n][ld]
+// buffers of pre-weighted messages p*xh_j.  tab_prev lists the previous iteration's sources
+// (self included, skipped here); NULL when nothing has been sent yet.
+// NM = number of messages per node known at compile time (0, 1, 2) or -1 for "read S at run time".
+// ------------------------------------------------------------------------------------------
+template <int V, bool NEST, bool ZOUT, int NM>
+__global__ __launch_bounds__(kBlock) void k_step_delay(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const float *__restrict__ msg_prev,
+    float *__restrict__ msg_cur, int n, size_t ld, size_t col0, long ncols,
+    const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
+{
+    typedef typename vec_of<V>::type T;
+    constexpr int M = NM > 0 ? NM : 1;
+    long c = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= ncols) return;
+    const size_t off = col0 + (size_t)c * V;
+
+    for (int i0 = 0; i0 < n; i0 += kBatch) {
+        T xv[kBatch], uv[kBatch], gv[kBatch], mv[kBatch][M];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (i0 + q < n) {
+                int i = i0 + q;
+                size_t a = (size_t)i * ld + off;
+                xv[q] = ld_stream<V>(x + a);
+                if (NEST) uv[q] = ld_stream<V>(u + a);
+                gv[q] = ld_stream<V>(g + a);
+                if (NM > 0) {
+                    // sources are sorted and contain i itself exactly once: drop it, keep order
+                    const int *src = tab_prev + (size_t)i * S;
+                    int taken = 0;
+#pragma unroll
+                    for (int s = 0; s < M + 1; ++s) {
+                        int j = src[s];
+                        if (j != i && taken < M) {
+                            mv[q][taken] = ld_cached<V>(msg_prev + (size_t)j * ld + off);
+                            ++taken;
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (i0 + q < n) {
+                int i = i0 + q;
+                size_t a = (size_t)i * ld + off;
+                T xh = half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
+                T own = p * xh;
+                st_stream<V>(msg_cur + a, own);
+                T acc = own;
+                if (NM > 0) {
+#pragma unroll
+                    for (int s = 0; s < M; ++s) acc = acc + mv[q][s];
+                } else if (NM < 0) {
+                    const int *src = tab_prev + (size_t)i * S;
+                    for (int s = 0; s < S; ++s) {
+                        int j = src[s];
+                        if (j != i) acc = acc + ld_cached<V>(msg_prev + (size_t)j * ld + off);
+                    }
+                }
+                st_stream<V>(x + a, acc);
+                if (ZOUT) st_stream<V>(z + a, debias_val<V>(acc, w[i]));
+            }
+        }
+    }
+}
+
+// Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
+// One block; every work-item reads before anyone writes.
+__global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p)
+{
+    int i = threadIdx.x;
+    float acc = 0.0f;
+    if (i < n) {
+        const int *src = tab + (size_t)i * S;
+        acc = p * w[src[0]];
+        for (int q = 1; q < S; ++q) {
+            float term = p * w[src[q]];
+            acc = acc + term;
+        }
+    }
+    __syncthreads();
+    if (i < n) w[i] = acc;
+}
+
+// Push-sum weights under one iteration of delay: own share now, the previous iteration's
+// messages (pre-weighted p*w_j) in ascending sender index; the share is also the new message.
+__global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *__restrict__ msgw_cur,
+                          int n, const int *__restrict__ tab_prev, int S, float p)
+{
+    int i = threadIdx.x;
+    float own = 0.0f, acc = 0.0f;
+    if (i < n) {
+        own = p * w[i];
+        acc = own;
+        if (tab_prev) {
+            const int *src = tab_prev + (size_t)i * S;
+            for (int q = 0; q < S; ++q) {
+                int j = src[q];
+                if (j != i) acc = acc + msgw_prev[j];
+            }
+        }
+    }
+    __syncthreads();
+    if (i < n) {
+        w[i] = acc;
+        msgw_cur[i] = own;
+    }
+}
+
+// z = x / w (Alg. 1 line 8) as a stand-alone pass; blockIdx.y = node.
+template <int V>
+__global__ __launch_bounds__(kBlock) void k_debias(const float *__restrict__ x,
+                                                  const float *__restrict__ w,
+                                                  float *__restrict__ z, size_t ld, size_t col0,
+                                                  long ncols)
+{
+    long c = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= ncols) return;
+    int i = blockIdx.y;
+    size_t a = (size_t)i * ld + col0 + (size_t)c * V;
+    st_stream<V>(z + a, debias_val<V>(ld_stream<V>(x + a), w[i]));
+}
+
+// ------------------------------------------------------------------------------------------
+// Consensus statistics: per node sum_e (z_i[e] - zbar[e])^2 with zbar the node-wise average.
+// |z_i - zbar| is typically orders of magnitude below |z_i|, so the differences are formed
+// against a reference row first: a_i = z_i - z_0 (exact or nearly so), abar = mean_i a_i, and the
+// squared terms are (a_i - abar)^2; every rounding error is then relative to the deviation
+// itself.  Partial sums: float per work-item and block, double from there on.
+// partial is [(n+1)][G]; row n carries sum_e zbar[e]^2.
+// ------------------------------------------------------------------------------------------
+constexpr int kStatsCache = 32;   // nodes whose z the small-n kernel keeps in registers
+
+template <int V>
+__global__ __launch_bounds__(kBlock) void k_stats_small(const float *__restrict__ z, int n,
+                                                       size_t ld, size_t col0, long ncols,
+                                                       long ntiles, float *__restrict__ partial,
+                                                       int G, int accumulate)
+{
+    typedef typename vec_of<V>::type T;
+    float acc[kStatsCache + 1];
+#pragma unroll
+    for (int i = 0; i <= kStatsCache; ++i) acc[i] = 0.0f;
+    const float inv_n = 1.0f / (float)n;
+
+    for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        long c = tile * kBlock + threadIdx.x;
+        if (c < ncols) {
+            const size_t off = col0 + (size_t)c * V;
+            T a[kStatsCache];
+#pragma unroll
+            for (int i = 0; i < kStatsCache; ++i)
+                if (i < n) a[i] = ld_stream<V>(z + (size_t)i * ld + off);
+            T ref = a[0];
+            T asum = T(0);
+#pragma unroll
+            for (int i = 0; i < kStatsCache; ++i)
+                if (i < n) {
+                    a[i] = a[i] - ref;
+                    asum = asum + a[i];
+                }
+            T abar = asum * inv_n;
+#pragma unroll
+            for (int i = 0; i < kStatsCache; ++i)
+                if (i < n) {
+                    T t = a[i] - abar;
+                    acc[i] += hsum(t * t);
+                }
+            T zb = ref + abar;
+            acc[kStatsCache] += hsum(zb * zb);
+        }
+    }
+
+    __shared__ float red[kBlock / 64][kStatsCache + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i <= kStatsCache; ++i) {
+        if (i < n || i == kStatsCache) {
+            float v = wave_sum(acc[i]);
+            if (lane == 0) red[wave][i] = v;
+        }
+    }
+    __syncthreads();
+    int i = threadIdx.x;
+    if (i <= kStatsCache && (i < n || i == kStatsCache)) {
+        float v = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
+        size_t row = (i == kStatsCache) ? (size_t)n : (size_t)i;
+        float *dst = partial + row * G + blockIdx.x;
+        *dst = accumulate ? *dst + v : v;
+    }
+}
+
+// Any n: two sweeps over the nodes (average first, then squared differences, re-reading z).
+template <int V>
+__global__ __launch_bounds__(kBlock) void k_stats_large(const float *__restrict__ z, int n,
+                                                       size_t ld, size_t col0, long ncols,
+                                                       long ntiles, float *__restrict__ partial,
+                                                       int G, int accumulate)
+{
+    typedef typename vec_of<V>::type T;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *red = reinterpret_cast<float *>(smem);          // [kBlock/64][n+1]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < (kBlock / 64) * (n + 1); i += kBlock) red[i] = 0.0f;
+    __syncthreads();
+    const float inv_n = 1.0f / (float)n;
+
+    for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        long c = tile * kBlock + threadIdx.x;
+        const bool active = c < ncols;
+        const size_t off = col0 + (size_t)(active ? c : 0) * V;
+        T ref = ld_cached<V>(z + off);
+        T asum = T(0);
+        for (int i = 1; i < n; ++i) {
+            T ai = ld_cached<V>(z + (size_t)i * ld + off) - ref;
+            asum = asum + ai;
+        }
+        T abar = asum * inv_n;
+        for (int i = 0; i < n; ++i) {
+            T ai = ld_cached<V>(z + (size_t)i * ld + off) - ref;
+            T t = ai - abar;
+            float v = wave_sum(active ? hsum(t * t) : 0.0f);
+            if (lane == 0) red[wave * (n + 1) + i] += v;
+        }
+        T zb = ref + abar;
+        float v = wave_sum(active ? hsum(zb * zb) : 0.0f);
+        if (lane == 0) red[wave * (n + 1) + n] += v;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i <= n; i += kBlock) {
+        float v = 0.0f;
+        for (int wv = 0; wv < kBlock / 64; ++wv) v += red[wv * (n + 1) + i];
+        float *dst = partial + (size_t)i * G + blockIdx.x;
+        *dst = accumulate ? *dst + v : v;
+    }
+}
+
+// Final reduction: out[0..6] = max, mean, min, sum w, ||zbar||, argmax, argmin; out[8+i] = dist_i.
+constexpr int kFinalBlock = 1024;
+__global__ __launch_bounds__(kFinalBlock) void k_stats_final(const float *__restrict__ partial, int G,
+                                                            int n, const float *__restrict__ w,
+                                                            double *__restrict__ out)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *sums = reinterpret_cast<double *>(smem);       // [n+1]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int row = wave; row <= n; row += kFinalBlock / 64) {
+        double s = 0.0;
+        for (int b = lane; b < G; b += 64) s += (double)partial[(size_t)row * G + b];
+        s = wave_sum(s);
+        if (lane == 0) sums[row] = s;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < n; i += kFinalBlock) out[8 + i] = sqrt(sums[i]);
+    if (threadIdx.x == 0) {
+        double dmax = 0.0, dmin = 0.0, dsum = 0.0, wsum = 0.0;
+        int amax = 0, amin = 0;
+        for (int i = 0; i < n; ++i) {
+            double di = sqrt(sums[i]);
+            if (i == 0 || di > dmax) { dmax = di; amax = i; }
+            if (i == 0 || di < dmin) { dmin = di; amin = i; }
+            dsum += di;
+            wsum += (double)w[i];
+        }
+        out[0] = dmax;
+        out[1] = dsum / (double)n;
+        out[2] = dmin;
+        out[3] = wsum;
+        out[4] = sqrt(sums[n]);
+        out[5] = (double)amax;
+        out[6] = (double)amin;
+        out[7] = 0.0;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_copy(floatx4 *__restrict__ dst,
+                                                const floatx4 *__restrict__ src, size_t count)
+{
+    size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < count) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// Handle
+// ------------------------------------------------------------------------------------------
+struct sgp_handle {
+    int n;
+    int64_t d, ld;
+    int topology, peers, delay;
+    int L;          // length of the peer list
+    int distinct;   // distinct out-peers per iteration (the same for every k)
+    int S;          // sources per receiver = distinct + 1
+
+    bool dev_ready;
+    int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
+    float *d_partial;   // [(n+1)][G] partial sums of the statistics
+    int G;
+    double *d_result;   // [8 + n]
+    double *h_result;   // pinned mirror
+    float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
+    float *d_msgw[2];   // overlap mode: pre-weighted weights p*w_j, [n] each
+    int cur;            // buffer that the NEXT step writes
+    bool have_msgs;
+    int64_t last_k;
+    int last_hip;
+};
+
+namespace {
+
+constexpr int kStatsGridMax = 2048;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+int hip_fail(sgp_handle *h, hipError_t e)
+{
+    if (h) h->last_hip = (int)e;
+    return SGP_ERR_HIP;
+}
+
+#define SGP_HIP_TRY(h, expr)                           \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail((h), e_); \
+    } while (0)
+
+// Sorted source lists of every receiver for each of the L distinct schedules.
+void build_tables(const sgp_handle *h, int *tab)
+{
+    const int n = h->n, S = h->S, tables = h->L > 0 ? h->L : 1;
+    for (int t = 0; t < tables; ++t) {
+        Schedule s = make_schedule(n, h->peers, t);
+        for (int i = 0; i < n; ++i) {
+            int *row = tab + ((size_t)t * n + i) * S;
+            int cnt = 0;
+            row[cnt++] = i;
+            for (int q = 0; q < s.distinct; ++q) row[cnt++] = (i - s.uniq[q] % n + n) % n;
+            for (int a = 1; a < cnt; ++a) {          // insertion sort, ascending
+                int v = row[a], b = a - 1;
+                while (b >= 0 && row[b] > v) { row[b + 1] = row[b]; --b; }
+                row[b + 1] = v;
+            }
+        }
+    }
+}
+
+int ensure_device(sgp_handle *h)
+{
+    if (h->dev_ready) return SGP_OK;
+    const int n = h->n, S = h->S, tables = h->L > 0 ? h->L : 1;
+    size_t tab_elems = (size_t)tables * n * S;
+    int *host_tab = static_cast<int *>(std::malloc(tab_elems * sizeof(int)));
+    if (!host_tab) return SGP_ERR_NOMEM;
+    build_tables(h, host_tab);
+    hipError_t e = hipMalloc(&h->d_tab, tab_elems * sizeof(int));
+    if (e == hipSuccess)
+        e = hipMemcpy(h->d_tab, host_tab, tab_elems * sizeof(int), hipMemcpyHostToDevice);
+    std::free(host_tab);
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+
+    h->G = kStatsGridMax;
+    e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)(8 + n) * sizeof(double));
+    if (e == hipSuccess)
+        e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)(8 + n) * sizeof(double),
+                          hipHostMallocDefault);
+    if (e == hipSuccess && h->delay) {
+        size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
+        for (int b = 0; b < 2 && e == hipSuccess; ++b) {
+            e = hipMalloc(&h->d_msg[b], bytes);
+            if (e == hipSuccess) e = hipMalloc(&h->d_msgw[b], (size_t)n * sizeof(float));
+        }
+    }
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+    h->dev_ready = true;
+    return SGP_OK;
+}
+
+void release_device(sgp_handle *h)
+{
+    if (h->d_tab) (void)hipFree(h->d_tab);
+    if (h->d_partial) (void)hipFree(h->d_partial);
+    if (h->d_result) (void)hipFree(h->d_result);
+    if (h->h_result) (void)hipHostFree(h->h_result);
+    for (int b = 0; b < 2; ++b) {
+        if (h->d_msg[b]) (void)hipFree(h->d_msg[b]);
+        if (h->d_msgw[b]) (void)hipFree(h->d_msgw[b]);
+    }
+}
+
+unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1) / block); }
+
+struct StepArgs {
+    float *x, *u, *z;
+    const float *g, *w;
+    int n;
+    size_t ld;
+    float p, gamma, mom;
+    hipStream_t stream;
+};
+
+template <int V, bool NEST, bool ZOUT>
+void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int ncyc, int len)
+{
+    hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kBlock)), dim3(kBlock), 0,
+                       a.stream, a.x, a.u, a.g, a.z, a.w, a.n, a.ld, col0, ncols, h, ncyc, len,
+                       a.p, a.gamma, a.mom);
+}
+
+template <int V, bool NEST, bool ZOUT>
+void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, int S)
+{
+    size_t lds = (size_t)a.n * kGatherBlock * V * sizeof(float);
+    hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT>), dim3(grid_for(ncols, kGatherBlock)),
+                       dim3(kGatherBlock), lds, a.stream, a.x, a.u, a.g, a.z, a.w, a.n, a.ld, col0,
+                       ncols, tab, S, a.p, a.gamma, a.mom);
+}
+
+template <int V, bool NEST, bool ZOUT>
+void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
+                  const int *tab_prev, int S)
+{
+    dim3 grid(grid_for(ncols, kBlock)), block(kBlock);
+    const int nm = tab_prev ? S - 1 : 0;
+    if (nm == 0)
+        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
+                           a.gamma, a.mom);
+    else if (nm == 1)
+        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
+                           a.gamma, a.mom);
+    else if (nm == 2)
+        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
+                           a.gamma, a.mom);
+    else
+        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
+                           a.gamma, a.mom);
+}
+
+// Calls f.template operator()<NEST, ZOUT>() for the run-time pair of flags.
+template <typename F>
+void dispatch_flags(bool nest, bool zout, F &&f)
+{
+    if (nest) {
+        if (zout) f.template operator()<true, true>();
+        else f.template operator()<true, false>();
+    } else {
+        if (zout) f.template operator()<false, true>();
+        else f.template operator()<false, false>();
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *sgp_status_string(int status)
+{
+    switch (status) {
+        case SGP_OK: return "SGP_OK";
+        case SGP_ERR_INVALID_ARG: return "SGP_ERR_INVALID_ARG";
+        case SGP_ERR_UNSUPPORTED: return "SGP_ERR_UNSUPPORTED";
+        case SGP_ERR_ALIGNMENT: return "SGP_ERR_ALIGNMENT";
+        case SGP_ERR_SEQUENCE: return "SGP_ERR_SEQUENCE";
+        case SGP_ERR_HIP: return "SGP_ERR_HIP";
+        case SGP_ERR_NOMEM: return "SGP_ERR_NOMEM";
+        default: return "SGP_ERR_UNKNOWN";
+    }
+}
+
+int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topology, int32_t peers,
+               int32_t delay)
+{
+    if (!out) return SGP_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n < 1 || n > SGP_MAX_NODES || d < 1 || ld < d || peers < 1 || peers > SGP_MAX_PEERS ||
+        delay < 0 || delay > 1)
+        return SGP_ERR_INVALID_ARG;
+    if (topology != SGP_TOPO_DIRECTED_EXP) return SGP_ERR_UNSUPPORTED;
+    sgp_handle *h = new (std::nothrow) sgp_handle();
+    if (!h) return SGP_ERR_NOMEM;
+    std::memset(h, 0, sizeof(*h));
+    h->n = n;
+    h->d = d;
+    h->ld = ld;
+    h->topology = topology;
+    h->peers = peers;
+    h->delay = delay;
+    Schedule s = make_schedule(n, peers, 0);
+    h->L = s.L;
+    h->distinct = s.distinct;
+    h->S = s.distinct + 1;
+    h->last_k = -1;
+    *out = h;
+    return SGP_OK;
+}
+
+int sgp_destroy(sgp_handle *h)
+{
+    if (!h) return SGP_OK;
+    int rc = SGP_OK;
+    if (h->dev_ready) {
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) rc = SGP_ERR_HIP;
+        release_device(h);
+    }
+    delete h;
+    return rc;
+}
+
+int sgp_reset(sgp_handle *h)
+{
+    if (!h) return SGP_ERR_INVALID_ARG;
+    h->have_msgs = false;
+    h->last_k = -1;
+    return SGP_OK;
+}
+
+int sgp_last_hip_error(const sgp_handle *h) { return h ? h->last_hip : 0; }
+
+int sgp_schedule(int32_t n, int32_t peers, int64_t k, int32_t *out_peers, int32_t *in_peers,
+                 float *weight)
+{
+    if (n < 1 || n > SGP_MAX_NODES || peers < 1 || peers > SGP_MAX_PEERS || k < 0)
+        return SGP_ERR_INVALID_ARG;
+    Schedule s = make_schedule(n, peers, k);
+    for (int i = 0; i < n; ++i)
+        for (int r = 0; r < peers; ++r) {
+            int hop = s.hop[r];
+            if (out_peers) out_peers[(size_t)i * peers + r] = hop < 0 ? -1 : (i + hop) % n;
+            if (in_peers) in_peers[(size_t)i * peers + r] = hop < 0 ? -1 : ((i - hop) % n + n) % n;
+        }
+    if (weight) *weight = s.p;
+    return SGP_OK;
+}
+
+int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_t *in_peers,
+                      float *weight)
+{
+    if (!h) return SGP_ERR_INVALID_ARG;
+    return sgp_schedule(h->n, h->peers, k, out_peers, in_peers, weight);
+}
+
+int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out, float gamma,
+             float momentum, int64_t k, void *stream)
+{
+    if (!h || !x || !w || !g || k < 0) return SGP_ERR_INVALID_ARG;
+    const bool nest = momentum != 0.0f;
+    if (nest && !m) return SGP_ERR_INVALID_ARG;
+    if (!aligned4(x) || !aligned4(w) || !aligned4(g) || (nest && !aligned4(m)) ||
+        (z_out && !aligned4(z_out)))
+        return SGP_ERR_ALIGNMENT;
+    if (z_out && (z_out == x || z_out == g || (nest && z_out == m))) return SGP_ERR_INVALID_ARG;
+    if (h->delay && h->have_msgs && k != h->last_k + 1) return SGP_ERR_SEQUENCE;
+
+    const int n = h->n, S = h->S;
+    const Schedule s = make_schedule(n, h->peers, k);
+    const int kmod = h->L > 0 ? (int)(k % h->L) : 0;
+    const bool gather = (h->delay == 0 && s.distinct > 1);
+    if (gather && n > 256) return SGP_ERR_UNSUPPORTED;
+
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m)) &&
+               (!z_out || aligned16(z_out));
+    if (gather && n > 64) vec = false;   // keep the LDS stash within 64 KiB
+    const long cols4 = vec ? (long)(h->d / 4) : 0;             // full 128-bit groups
+    const size_t tail0 = (size_t)cols4 * 4;
+    const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
+
+    StepArgs a{x, m, z_out, g, w, n, (size_t)h->ld, s.p, gamma, momentum, st};
+    const int *tab_k = h->d_tab + (size_t)kmod * n * S;
+    const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
+
+    if (h->delay == 0) {
+        // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
+        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p);
+        if (!gather) {
+            const int hop = s.distinct ? s.uniq[0] % n : 0;
+            const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
+            const int len = n / ncyc;
+            dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+                if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, ncyc, len);
+                if (tail > 0) launch_one_peer<1, NEST, ZOUT>(a, tail0, tail, hop, ncyc, len);
+            });
+        } else {
+            dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+                if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, tab_k, S);
+                if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, tab_k, S);
+            });
+        }
+    } else {
+        const int *tab_prev = nullptr;
+        if (h->have_msgs && h->L > 0) {
+            const int kprev = (int)((k - 1) % h->L);
+            tab_prev = h->d_tab + (size_t)kprev * n * S;
+        }
+        const int cur = h->cur, prv = cur ^ 1;
+        hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
+                           n, tab_prev, S, s.p);
+        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+            if (cols4 > 0)
+                launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S);
+            if (tail > 0)
+                launch_delay<1, NEST, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S);
+        });
+        h->cur = prv;
+        h->have_msgs = true;
+        h->last_k = k;
+    }
+    SGP_HIP_TRY(h, hipGetLastError());
+    return SGP_OK;
+}
+
+int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *stream)
+{
+    if (!h || !x || !w || !z) return SGP_ERR_INVALID_ARG;
+    if (!aligned4(x) || !aligned4(w) || !aligned4(z)) return SGP_ERR_ALIGNMENT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(z);
+    const long cols4 = vec ? (long)(h->d / 4) : 0;
+    const size_t tail0 = (size_t)cols4 * 4;
+    const long tail = (long)(h->d - (int64_t)tail0);
+    if (cols4 > 0)
+        hipLaunchKernelGGL(k_debias<4>, dim3(grid_for(cols4, kBlock), h->n), dim3(kBlock), 0, st, x, w,
+                           z, (size_t)h->ld, (size_t)0, cols4);
+    if (tail > 0)
+        hipLaunchKernelGGL(k_debias<1>, dim3(grid_for(tail, kBlock), h->n), dim3(kBlock), 0, st, x, w,
+                           z, (size_t)h->ld, tail0, tail);
+    SGP_HIP_TRY(h, hipGetLastError());
+    return SGP_OK;
+}
+
+int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
+                        double *per_node_dist_host, void *stream)
+{
+    if (!h || !z || !w || !host_out) return SGP_ERR_INVALID_ARG;
+    if (!aligned4(z) || !aligned4(w)) return SGP_ERR_ALIGNMENT;
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n = h->n;
+    const bool vec = (h->ld % 4 == 0) && aligned16(z);
+    const long cols4 = vec ? (long)(h->d / 4) : 0;
+    const size_t tail0 = (size_t)cols4 * 4;
+    const long tail = (long)(h->d - (int64_t)tail0);
+    const int G = h->G;
+    const size_t lds_large = (size_t)(kBlock / 64) * (n + 1) * sizeof(float);
+
+    // every block writes its column of the partial table; blocks beyond the tile count write 0
+    bool first = true;
+    auto run = [&](auto vtag, size_t col0, long ncols) {
+        constexpr int V = decltype(vtag)::value;
+        long ntiles = (ncols + kBlock - 1) / kBlock;
+        int acc = first ? 0 : 1;
+        if (n <= kStatsCache)
+            hipLaunchKernelGGL(k_stats_small<V>, dim3(G), dim3(kBlock), 0, st, z, n, (size_t)h->ld,
+                               col0, ncols, ntiles, h->d_partial, G, acc);
+        else
+            hipLaunchKernelGGL(k_stats_large<V>, dim3(G), dim3(kBlock), lds_large, st, z, n,
+                               (size_t)h->ld, col0, ncols, ntiles, h->d_partial, G, acc);
+        first = false;
+    };
+    if (cols4 > 0) run(std::integral_constant<int, 4>{}, 0, cols4);
+    if (tail > 0) run(std::integral_constant<int, 1>{}, tail0, tail);
+    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(kFinalBlock), (size_t)(n + 1) * sizeof(double), st,
+                       h->d_partial, G, n, w, h->d_result);
+    SGP_HIP_TRY(h, hipGetLastError());
+    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
+                                  hipMemcpyDeviceToHost, st));
+    SGP_HIP_TRY(h, hipStreamSynchronize(st));
+    host_out->dist_max = h->h_result[0];
+    host_out->dist_mean = h->h_result[1];
+    host_out->dist_min = h->h_result[2];
+    host_out->w_sum = h->h_result[3];
+    host_out->zbar_norm = h->h_result[4];
+    host_out->argmax = (int32_t)h->h_result[5];
+    host_out->argmin = (int32_t)h->h_result[6];
+    if (per_node_dist_host)
+        for (int i = 0; i < n; ++i) per_node_dist_host[i] = h->h_result[8 + i];
+    return SGP_OK;
+}
+
+int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes < 0 || (nbytes & 15) || !aligned16(dst) || !aligned16(src))
+        return SGP_ERR_INVALID_ARG;
+    if (nbytes == 0) return SGP_OK;
+    size_t count = (size_t)nbytes / 16;
+    size_t blocks = (count + kBlock - 1) / kBlock;
+    if (blocks > 0x7fffffffu) return SGP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_copy, dim3((unsigned)blocks), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
+                       static_cast<floatx4 *>(dst), static_cast<const floatx4 *>(src), count);
+    if (hipGetLastError() != hipSuccess) return SGP_ERR_HIP;
+    return SGP_OK;
+}
+
+}  // extern "C"

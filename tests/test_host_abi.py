@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments, and its integer peer scheduler agrees bit for bit with the
+positions of the non-zeros of the oracle's dense mixing matrix."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sgp_oracle as O
+import paper_1811_10792_amd as sgp
+from paper_1811_10792_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1811_10792_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "sgp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sgp_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    assert binding.status_string(0) == "SGP_OK"
+    names = {binding.status_string(c) for c in range(-6, 1)}
+    assert len(names) == 7 and all(s.startswith("SGP_") for s in names)
+    assert binding.status_string(-99) == "SGP_ERR_UNKNOWN"
+
+
+def test_create_validates_arguments(lib):
+    h = ctypes.c_void_p()
+    ok = lambda *a: lib.sgp_create(ctypes.byref(h), *a)
+    assert ok(4, 16, 16, 0, 1, 0) == 0 and h.value
+    assert lib.sgp_destroy(h) == 0
+    for bad in ((0, 16, 16, 0, 1, 0), (4, 0, 16, 0, 1, 0), (4, 16, 8, 0, 1, 0), (4, 16, 16, 0, 0, 0),
+                (4, 16, 16, 0, 17, 0), (4, 16, 16, 0, 1, 2), (1025, 16, 16, 0, 1, 0)):
+        assert ok(*bad) == binding.SGP_ERR_INVALID_ARG and not h.value
+    assert ok(4, 16, 16, 7, 1, 0) == binding.SGP_ERR_UNSUPPORTED
+    assert lib.sgp_create(None, 4, 16, 16, 0, 1, 0) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_destroy(None) == 0
+
+
+def test_null_pointers_are_rejected_before_any_launch(lib):
+    h = ctypes.c_void_p()
+    assert lib.sgp_create(ctypes.byref(h), 4, 16, 16, 0, 1, 0) == 0
+    assert lib.sgp_step(h, None, None, None, None, None, 0.1, 0.9, 0, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_step(None, 16, 16, 16, 16, None, 0.1, 0.9, 0, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_step(h, 16, 16, None, 16, None, 0.1, 0.9, 0, None) == binding.SGP_ERR_INVALID_ARG  # momentum without m
+    assert lib.sgp_step(h, 16, 16, 16, 16, None, 0.1, 0.9, -1, None) == binding.SGP_ERR_INVALID_ARG  # k < 0
+    assert lib.sgp_step(h, 18, 16, 16, 16, None, 0.1, 0.9, 0, None) == binding.SGP_ERR_ALIGNMENT
+    assert lib.sgp_debias(h, None, None, None, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_consensus_stats(h, None, None, None, None, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_copy(None, None, 16, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_copy(16, 32, 8, None) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_destroy(h) == 0
+
+
+@pytest.mark.parametrize("peers", [1, 2, 3])
+def test_schedule_matches_oracle_nonzeros_exactly(lib, peers):
+    for n in list(range(1, 18)) + [31, 32, 33, 64, 100]:
+        L = (n - 1).bit_length()
+        for k in list(range(0, 2 * L + 2)) + [10 ** 6 + 3, 2 ** 40 + 5]:
+            outp, inp, wt = sgp.sgp_schedule(n, peers, k)
+            P32 = O.mixing_matrix(n, peers, k, np.float32)
+            for i in range(n):
+                senders_to = {j for j in outp[i] if j >= 0} | {i}
+                hears_from = {j for j in inp[i] if j >= 0} | {i}
+                assert senders_to == set(np.nonzero(P32[:, i])[0].tolist())   # column i: receivers
+                assert hears_from == set(np.nonzero(P32[i, :])[0].tolist())   # row i: senders
+            assert np.float32(wt) == P32[0, 0]                               # same float32 bits
+            assert set(np.unique(P32[P32 != 0]).tolist()) == {float(np.float32(wt))}
+
+
+def test_schedule_slots_and_duplicates(lib):
+    outp, inp, wt = sgp.sgp_schedule(8, 2, 1)            # hops 2 and 4
+    assert outp[0] == [2, 4] and inp[0] == [6, 4] and wt == np.float32(1.0) / np.float32(3.0)
+    outp, inp, wt = sgp.sgp_schedule(2, 2, 0)            # the only peer, reached twice
+    assert outp == [[1, -1], [0, -1]] and wt == 0.5
+    outp, inp, wt = sgp.sgp_schedule(1, 1, 4)
+    assert outp == [[-1]] and inp == [[-1]] and wt == 1.0
+    # printed example: 8 nodes, node 0 sends to 1, 2, 4 over iterations 0, 1, 2, then wraps
+    assert [sgp.sgp_schedule(8, 1, k)[0][0][0] for k in range(4)] == [1, 2, 4, 1]
+
+
+def test_handle_schedule_equals_handle_free(lib):
+    s = sgp.SGP(12, 40, peers=2)
+    for k in range(9):
+        assert s.peer_schedule(k) == sgp.sgp_schedule(12, 2, k)
+    s.close()
