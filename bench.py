@@ -107,12 +107,13 @@ def main():
     n, d = wl.n, wl.d
     torch.cuda.set_device(0)
     nest = wl.momentum != 0.0
-    eng = sgp.SGP(n, d, peers=wl.peers, delay=wl.delay)
-    X = syn.device_normal(n, d, wl.x_std, wl.seed, 3)
+    ld = syn.padded_ld(d)                 # rows start on 1 KiB boundaries
+    eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3)
     U = torch.zeros_like(X)
     W = torch.ones(n, dtype=torch.float32, device="cuda")
     Z = torch.empty_like(X)
-    pool = [syn.device_normal(n, d, wl.grad_std, wl.seed, 100 + i) for i in range(max(1, args.pool))]
+    pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i) for i in range(max(1, args.pool))]
     do_stats = wl.stats_each_step and not args.no_stats
     stream = torch.cuda.current_stream()
 
@@ -152,7 +153,7 @@ def main():
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "n": n, "d": d, "peers": wl.peers, "delay": wl.delay,
+        "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "peers": wl.peers, "delay": wl.delay,
                    "momentum": wl.momentum, "gamma": wl.gamma,
                    "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool)},
         "roofline": {"bound": "hbm", "kernel": "fused sgp_step kernel",

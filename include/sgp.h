@@ -17,7 +17,10 @@
  *         stride ld >= d elements; only the first d elements of a row are read or written.
  *     w : [n].
  * The fast path needs ld % 4 == 0 and 16-byte aligned base pointers (128-bit accesses);
- * otherwise a scalar path is used.  Arithmetic is IEEE binary32, round to nearest even, every
+ * otherwise a scalar path is used.  For full bandwidth choose ld as a multiple of 256 elements so
+ * that every row starts on a 1 KiB boundary: rows that start off a 128-byte boundary split each
+ * wavefront's 1 KiB access over an extra cache line and cost about 15 % of the achieved HBM
+ * bandwidth (measured on MI355X).  Arithmetic is IEEE binary32, round to nearest even, every
  * operation rounded separately (no fused multiply-add), correctly rounded division, subnormals
  * kept.  Sums over senders are taken in ascending sender index.
  *

@@ -22,6 +22,20 @@
 
 #pragma clang fp contract(off)
 
+// Tuning knobs (overridable at build time for tuning runs).
+#ifndef SGP_OP_BLOCK
+#define SGP_OP_BLOCK 256
+#endif
+#ifndef SGP_OP_COLS
+#define SGP_OP_COLS 4
+#endif
+#ifndef SGP_NT_LOAD
+#define SGP_NT_LOAD 1
+#endif
+#ifndef SGP_NT_STORE
+#define SGP_NT_STORE 1
+#endif
+
 namespace {
 
 // ------------------------------------------------------------------------------------------
@@ -83,12 +97,20 @@ template <> struct vec_of<1> { typedef float type; };
 template <int V>
 __device__ __forceinline__ typename vec_of<V>::type ld_stream(const float *p)
 {
+#if SGP_NT_LOAD
     return __builtin_nontemporal_load(reinterpret_cast<const typename vec_of<V>::type *>(p));
+#else
+    return *reinterpret_cast<const typename vec_of<V>::type *>(p);
+#endif
 }
 template <int V>
 __device__ __forceinline__ void st_stream(float *p, typename vec_of<V>::type v)
 {
+#if SGP_NT_STORE
     __builtin_nontemporal_store(v, reinterpret_cast<typename vec_of<V>::type *>(p));
+#else
+    *reinterpret_cast<typename vec_of<V>::type *>(p) = v;
+#endif
 }
 template <int V>
 __device__ __forceinline__ typename vec_of<V>::type ld_cached(const float *p)
@@ -135,17 +157,23 @@ __device__ __forceinline__ typename vec_of<V>::type half_step(typename vec_of<V>
     }
 }
 
-// z = x / w, IEEE division; w == 1 (every non-delayed regular graph) needs no division at all,
-// and x / 1 == x bit for bit.
-template <int V>
+// z = x / w, IEEE division.  When every weight is exactly 1 (any doubly-stochastic schedule
+// started from w = 1, i.e. every non-delayed regular graph) the division is the identity bit for
+// bit; the weight kernel records that in a device flag and the step kernels then run a copy of
+// their loop without the division (DIV = false).
+template <int V, bool DIV>
 __device__ __forceinline__ typename vec_of<V>::type debias_val(typename vec_of<V>::type xn, float wi)
 {
-    return wi == 1.0f ? xn : xn / wi;
+    if (DIV) return xn / wi;
+    return xn;
 }
 
 constexpr int kBlock = 256;     // work-items per block of the streaming kernels
 constexpr int kGatherBlock = 64;
 constexpr int kBatch = 4;       // nodes whose loads are issued back to back before any use
+
+constexpr int kOpBlock = SGP_OP_BLOCK;   // work-items per block
+constexpr int kOpCols = SGP_OP_COLS;     // 128-bit column groups per work-item
 
 // ------------------------------------------------------------------------------------------
 // Fused step, one out-peer (or none, n == 1).  The in-neighbour of node i is (i - h) mod n, so
@@ -154,63 +182,142 @@ constexpr int kBatch = 4;       // nodes whose loads are issued back to back bef
 //   x_new[i] = p*xh[i] + p*xh[(i-h) mod n]   (two exactly-rounded products; their sum does not
 //                                             depend on the order of the two terms)
 // ------------------------------------------------------------------------------------------
-template <int V, bool NEST, bool ZOUT>
-__global__ __launch_bounds__(kBlock) void k_step_one_peer(
+// The walk is software-pipelined.  On gfx9-family parts loads and stores share one in-order
+// completion counter, so a wave that waits for freshly issued loads also waits for the write
+// acknowledgements of every store issued before them.  Issuing the NEXT node's loads before the
+// current node's stores keeps the stores out of that wait.  The walk over all cycles is
+// flattened so that the pipeline never drains at a cycle boundary (hop n/2 has n/2 cycles of 2).
+template <int V, bool NEST, int C>
+struct RowRegs {
+    typename vec_of<V>::type x[C], u[C], g[C];
+    float w;
+    int node;
+};
+
+struct WalkPos {
+    int cyc, pos, node;
+    __device__ __forceinline__ void advance(int n, int h, int len)
+    {
+        if (++pos == len) {
+            pos = 0;
+            node = ++cyc;
+        } else {
+            node += h;
+            if (node >= n) node -= n;
+        }
+    }
+};
+
+template <int V, bool NEST, bool ZOUT, bool DIV>
+__device__ __forceinline__ void one_peer_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
-    long ncols, int h, int ncyc, int len, float p, float gamma, float mom)
+    long ncols, int h, int len, float p, float gamma, float mom)
 {
     typedef typename vec_of<V>::type T;
-    long c = (long)blockIdx.x * kBlock + threadIdx.x;
-    if (c >= ncols) return;
-    const size_t off = col0 + (size_t)c * V;
-
-    for (int cyc = 0; cyc < ncyc; ++cyc) {
-        int node = cyc;
-        T first = T(0), prev = T(0);
-        for (int t0 = 0; t0 < len; t0 += kBatch) {
-            T xv[kBatch], uv[kBatch], gv[kBatch];
-            int nd[kBatch];
+    constexpr int C = kOpCols;
+    const long cbase = (long)blockIdx.x * (kOpBlock * C) + threadIdx.x;
+    size_t off[C];
+    bool live[C];
 #pragma unroll
-            for (int q = 0; q < kBatch; ++q) {
-                nd[q] = node;
-                if (t0 + q < len) {
-                    size_t a = (size_t)node * ld + off;
-                    xv[q] = ld_stream<V>(x + a);
-                    if (NEST) uv[q] = ld_stream<V>(u + a);
-                    gv[q] = ld_stream<V>(g + a);
-                    node += h;
-                    if (node >= n) node -= n;
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < kBatch; ++q) {
-                if (t0 + q < len) {
-                    size_t a = (size_t)nd[q] * ld + off;
-                    T xh = half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
-                    if (t0 + q == 0) {
-                        first = xh;
-                    } else {
-                        T a0 = p * xh;
-                        T a1 = p * prev;
-                        T xn = a0 + a1;
-                        st_stream<V>(x + a, xn);
-                        if (ZOUT) st_stream<V>(z + a, debias_val<V>(xn, w[nd[q]]));
-                    }
-                    prev = xh;
-                }
-            }
-        }
-        // close the cycle: its first node hears from the last one visited
-        size_t a = (size_t)cyc * ld + off;
-        T xn = p * first;
-        if (len > 1) {
-            T a1 = p * prev;
-            xn = xn + a1;
-        }
-        st_stream<V>(x + a, xn);
-        if (ZOUT) st_stream<V>(z + a, debias_val<V>(xn, w[cyc]));
+    for (int j = 0; j < C; ++j) {
+        long c = cbase + (long)j * kOpBlock;
+        live[j] = c < ncols;
+        off[j] = col0 + (size_t)(live[j] ? c : 0) * V;
     }
+    if (!live[0]) return;
+
+    auto load_row = [&](RowRegs<V, NEST, C> &r, int node) {
+        r.node = node;
+        r.w = (ZOUT && DIV) ? w[node] : 1.0f;
+        const size_t row = (size_t)node * ld;
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                r.x[j] = ld_stream<V>(x + row + off[j]);
+                if (NEST) r.u[j] = ld_stream<V>(u + row + off[j]);
+                r.g[j] = ld_stream<V>(g + row + off[j]);
+            }
+    };
+
+    T first[C], prev[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) first[j] = prev[j] = T(0);
+    int first_node = 0;
+    float first_w = 1.0f;
+    int ppos = 0;   // position of the node being processed within its cycle
+
+    auto process_row = [&](const RowRegs<V, NEST, C> &r) {
+        const size_t row = (size_t)r.node * ld;
+        const bool opens = (ppos == 0), closes = (ppos == len - 1);
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                const size_t a = row + off[j];
+                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom, u + a);
+                if (opens) {
+                    first[j] = xh;
+                } else {
+                    T a0 = p * xh;
+                    T a1 = p * prev[j];
+                    T xn = a0 + a1;
+                    st_stream<V>(x + a, xn);
+                    if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(xn, r.w));
+                }
+                prev[j] = xh;
+            }
+        if (opens) {
+            first_node = r.node;
+            first_w = r.w;
+        }
+        if (closes) {   // the first node of the cycle hears from the last one visited
+            const size_t frow = (size_t)first_node * ld;
+#pragma unroll
+            for (int j = 0; j < C; ++j)
+                if (live[j]) {
+                    const size_t a = frow + off[j];
+                    T xn = p * first[j];
+                    if (len > 1) {
+                        T a1 = p * prev[j];
+                        xn = xn + a1;
+                    }
+                    st_stream<V>(x + a, xn);
+                    if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(xn, first_w));
+                }
+            ppos = 0;
+        } else {
+            ++ppos;
+        }
+    };
+
+    WalkPos lp{0, 0, 0};
+    RowRegs<V, NEST, C> ra, rb;
+    load_row(ra, lp.node);
+    lp.advance(n, h, len);
+    for (int t = 0; t < n; t += 2) {
+        if (t + 1 < n) {
+            load_row(rb, lp.node);
+            lp.advance(n, h, len);
+        }
+        process_row(ra);
+        if (t + 2 < n) {
+            load_row(ra, lp.node);
+            lp.advance(n, h, len);
+        }
+        if (t + 1 < n) process_row(rb);
+    }
+}
+
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kOpBlock) void k_step_one_peer(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
+    size_t ld, size_t col0, long ncols, int h, int len, float p, float gamma, float mom)
+{
+    if (ZOUT && *unit_w == 0)
+        one_peer_body<V, NEST, ZOUT, true>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom);
+    else
+        one_peer_body<V, NEST, ZOUT, false>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -218,8 +325,8 @@ __global__ __launch_bounds__(kBlock) void k_step_one_peer(
 // private LDS column (no barrier: a work-item only reads what it wrote), then each receiver sums
 // its sources.  tab[i*S + q], q < S, lists node i's sources (itself included) in ascending index.
 // ------------------------------------------------------------------------------------------
-template <int V, bool NEST, bool ZOUT>
-__global__ __launch_bounds__(kGatherBlock) void k_step_gather(
+template <int V, bool NEST, bool ZOUT, bool DIV>
+__device__ __forceinline__ void gather_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
     long ncols, const int *__restrict__ tab, int S, float p, float gamma, float mom)
@@ -260,8 +367,21 @@ __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
         }
         size_t a = (size_t)i * ld + off;
         st_stream<V>(x + a, acc);
-        if (ZOUT) st_stream<V>(z + a, debias_val<V>(acc, w[i]));
+        if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(acc, DIV ? w[i] : 1.0f));
     }
+}
+
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kGatherBlock) void k_step_gather(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
+    size_t ld, size_t col0, long ncols, const int *__restrict__ tab, int S, float p, float gamma,
+    float mom)
+{
+    if (ZOUT && *unit_w == 0)
+        gather_body<V, NEST, ZOUT, true>(x, u, g, z, w, n, ld, col0, ncols, tab, S, p, gamma, mom);
+    else
+        gather_body<V, NEST, ZOUT, false>(x, u, g, z, w, n, ld, col0, ncols, tab, S, p, gamma, mom);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -272,8 +392,8 @@ __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
 // (self included, skipped here); NULL when nothing has been sent yet.
 // NM = number of messages per node known at compile time (0, 1, 2) or -1 for "read S at run time".
 // ------------------------------------------------------------------------------------------
-template <int V, bool NEST, bool ZOUT, int NM>
-__global__ __launch_bounds__(kBlock) void k_step_delay(
+template <int V, bool NEST, bool ZOUT, int NM, bool DIV>
+__device__ __forceinline__ void delay_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const float *__restrict__ msg_prev,
     float *__restrict__ msg_cur, int n, size_t ld, size_t col0, long ncols,
@@ -330,15 +450,31 @@ __global__ __launch_bounds__(kBlock) void k_step_delay(
                     }
                 }
                 st_stream<V>(x + a, acc);
-                if (ZOUT) st_stream<V>(z + a, debias_val<V>(acc, w[i]));
+                if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(acc, DIV ? w[i] : 1.0f));
             }
         }
     }
 }
 
+template <int V, bool NEST, bool ZOUT, int NM>
+__global__ __launch_bounds__(kBlock) void k_step_delay(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w,
+    const float *__restrict__ msg_prev, float *__restrict__ msg_cur, int n, size_t ld, size_t col0,
+    long ncols, const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
+{
+    if (ZOUT && *unit_w == 0)
+        delay_body<V, NEST, ZOUT, NM, true>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols,
+                                            tab_prev, S, p, gamma, mom);
+    else
+        delay_body<V, NEST, ZOUT, NM, false>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols,
+                                             tab_prev, S, p, gamma, mom);
+}
+
 // Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
 // One block; every work-item reads before anyone writes.
-__global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p)
+__global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p,
+                        int *__restrict__ unit_w)
 {
     int i = threadIdx.x;
     float acc = 0.0f;
@@ -350,14 +486,16 @@ __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, flo
             acc = acc + term;
         }
     }
-    __syncthreads();
+    const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
     if (i < n) w[i] = acc;
+    if (i == 0) *unit_w = all_one;
 }
 
 // Push-sum weights under one iteration of delay: own share now, the previous iteration's
 // messages (pre-weighted p*w_j) in ascending sender index; the share is also the new message.
 __global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *__restrict__ msgw_cur,
-                          int n, const int *__restrict__ tab_prev, int S, float p)
+                          int n, const int *__restrict__ tab_prev, int S, float p,
+                          int *__restrict__ unit_w)
 {
     int i = threadIdx.x;
     float own = 0.0f, acc = 0.0f;
@@ -372,11 +510,12 @@ __global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *
             }
         }
     }
-    __syncthreads();
+    const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
     if (i < n) {
         w[i] = acc;
         msgw_cur[i] = own;
     }
+    if (i == 0) *unit_w = all_one;
 }
 
 // z = x / w (Alg. 1 line 8) as a stand-alone pass; blockIdx.y = node.
@@ -390,7 +529,9 @@ __global__ __launch_bounds__(kBlock) void k_debias(const float *__restrict__ x,
     if (c >= ncols) return;
     int i = blockIdx.y;
     size_t a = (size_t)i * ld + col0 + (size_t)c * V;
-    st_stream<V>(z + a, debias_val<V>(ld_stream<V>(x + a), w[i]));
+    const float wi = w[i];
+    typename vec_of<V>::type xv = ld_stream<V>(x + a);
+    st_stream<V>(z + a, wi == 1.0f ? xv : xv / wi);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -567,6 +708,7 @@ struct sgp_handle {
 
     bool dev_ready;
     int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
+    int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
     int G;
     double *d_result;   // [8 + n]
@@ -633,7 +775,8 @@ int ensure_device(sgp_handle *h)
     if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
 
     h->G = kStatsGridMax;
-    e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
+    e = hipMalloc(&h->d_unit_w, sizeof(int));
+    if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)(8 + n) * sizeof(double));
     if (e == hipSuccess)
         e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)(8 + n) * sizeof(double),
@@ -653,6 +796,7 @@ int ensure_device(sgp_handle *h)
 void release_device(sgp_handle *h)
 {
     if (h->d_tab) (void)hipFree(h->d_tab);
+    if (h->d_unit_w) (void)hipFree(h->d_unit_w);
     if (h->d_partial) (void)hipFree(h->d_partial);
     if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
@@ -667,6 +811,7 @@ unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1)
 struct StepArgs {
     float *x, *u, *z;
     const float *g, *w;
+    const int *unit_w;
     int n;
     size_t ld;
     float p, gamma, mom;
@@ -674,11 +819,12 @@ struct StepArgs {
 };
 
 template <int V, bool NEST, bool ZOUT>
-void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int ncyc, int len)
+void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
-    hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kBlock)), dim3(kBlock), 0,
-                       a.stream, a.x, a.u, a.g, a.z, a.w, a.n, a.ld, col0, ncols, h, ncyc, len,
-                       a.p, a.gamma, a.mom);
+    hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
+                       dim3(kOpBlock), 0,
+                       a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
+                       len, a.p, a.gamma, a.mom);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -686,8 +832,8 @@ void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, i
 {
     size_t lds = (size_t)a.n * kGatherBlock * V * sizeof(float);
     hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT>), dim3(grid_for(ncols, kGatherBlock)),
-                       dim3(kGatherBlock), lds, a.stream, a.x, a.u, a.g, a.z, a.w, a.n, a.ld, col0,
-                       ncols, tab, S, a.p, a.gamma, a.mom);
+                       dim3(kGatherBlock), lds, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld,
+                       col0, ncols, tab, S, a.p, a.gamma, a.mom);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -698,20 +844,20 @@ void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_p
     const int nm = tab_prev ? S - 1 : 0;
     if (nm == 0)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
-                           a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+                           a.p, a.gamma, a.mom);
     else if (nm == 1)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
-                           a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+                           a.p, a.gamma, a.mom);
     else if (nm == 2)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
-                           a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+                           a.p, a.gamma, a.mom);
     else
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S, a.p,
-                           a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+                           a.p, a.gamma, a.mom);
 }
 
 // Calls f.template operator()<NEST, ZOUT>() for the run-time pair of flags.
@@ -850,20 +996,20 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
 
-    StepArgs a{x, m, z_out, g, w, n, (size_t)h->ld, s.p, gamma, momentum, st};
+    StepArgs a{x, m, z_out, g, w, h->d_unit_w, n, (size_t)h->ld, s.p, gamma, momentum, st};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
 
     if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
-        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p);
+        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w);
         if (!gather) {
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
             const int len = n / ncyc;
             dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-                if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, ncyc, len);
-                if (tail > 0) launch_one_peer<1, NEST, ZOUT>(a, tail0, tail, hop, ncyc, len);
+                if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, len);
+                if (tail > 0) launch_one_peer<1, NEST, ZOUT>(a, tail0, tail, hop, len);
             });
         } else {
             dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
@@ -879,7 +1025,7 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
         }
         const int cur = h->cur, prv = cur ^ 1;
         hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
-                           n, tab_prev, S, s.p);
+                           n, tab_prev, S, s.p, h->d_unit_w);
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0)
                 launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S);

@@ -47,6 +47,12 @@ WORKLOADS = {
 }
 
 
+def padded_ld(d: int, multiple: int = 256) -> int:
+    """Row stride used by the benchmark and the full-size tests: d rounded up to a multiple of 256
+    elements, so that every node's row starts on a 1 KiB boundary."""
+    return (d + multiple - 1) // multiple * multiple
+
+
 def _rng(seed: int, *stream: int) -> np.random.Generator:
     return np.random.default_rng([int(seed), *[int(s) for s in stream]])
 
@@ -96,7 +102,8 @@ def initial_state(wl: Workload):
 # ---- device-side generators for the model-sized workloads (torch used for memory only) -------
 
 def device_normal(n: int, ld: int, std: float, seed: int, stream: int, device="cuda"):
-    """float32 [n, ld] N(0, std) tensor drawn on the device from a seeded generator."""
+    """float32 [n, ld] N(0, std) tensor drawn on the device from a seeded generator (padding
+    columns, if ld exceeds d, are drawn too; the library never touches them)."""
     import torch
     gen = torch.Generator(device=device)
     gen.manual_seed((int(seed) * 1_000_003 + int(stream)) & 0x7FFFFFFFFFFFFFFF)

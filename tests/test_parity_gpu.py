@@ -285,19 +285,21 @@ def _full_size_spot_check(wl, steps, count=3000):
     the oracle recomputes a sample of coordinates (coordinates are independent, so a column
     slice of the oracle is exact), including the first tile and the ragged tail."""
     n, d = wl.n, wl.d
+    ld = syn.padded_ld(d)                                      # the benchmark's row stride
     torch.cuda.empty_cache()
-    X = syn.device_normal(n, d, wl.x_std, wl.seed, 3)
-    U = syn.device_normal(n, d, wl.grad_std, wl.seed, 6)      # a non-trivial momentum buffer
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3)
+    U = syn.device_normal(n, ld, wl.grad_std, wl.seed, 6)     # a non-trivial momentum buffer
     W = torch.ones(n, dtype=torch.float32, device=DEV)
     Z = torch.empty_like(X)
     cols = syn.sample_columns(d, count, wl.seed)
     cidx = torch.from_numpy(cols).to(DEV)
     xo, uo = host(X[:, cidx]), host(U[:, cidx])
     wo = np.ones(n, np.float32)
-    eng = sgp.SGP(n, d, peers=wl.peers, delay=wl.delay)
+    eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
     st = O.Delay1State(n, len(cols), np.float32) if wl.delay else None
+    pad0 = [host(T[:, d:]).copy() for T in (X, U)]
     for k in range(steps):
-        G = syn.device_normal(n, d, wl.grad_std, wl.seed, 100 + k)
+        G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + k)
         g = host(G[:, cidx])
         eng.step(X, W, U, G, Z, wl.gamma, wl.momentum, k)
         P = O.mixing_matrix(n, wl.peers, k, np.float32)
@@ -316,12 +318,14 @@ def _full_size_spot_check(wl, steps, count=3000):
         s_full = eng.consensus_stats(Z, W, per_node=True)
         assert s_full.dist_min > 0 and s_full.w_sum == n
         dsl = 1 << 20
-        sl = sgp.SGP(n, dsl, d)
-        s = sl.consensus_stats(Z, W, per_node=True)           # first 2^20 coordinates, stride d
+        sl = sgp.SGP(n, dsl, ld)
+        s = sl.consensus_stats(Z, W, per_node=True)           # first 2^20 coordinates, stride ld
         dist, ref = O.consensus_stats(host(Z[:, :dsl]), wo)
         assert np.abs(np.array(s.per_node) - dist).max() <= 1e-5 * dist.max()
         assert abs(s.dist_max - ref["max"]) <= 1e-5 * ref["max"]
         sl.close()
+    for T, p0 in zip((X, U), pad0):                            # padding columns stay untouched
+        assert np.array_equal(host(T[:, d:]), p0)
     eng.close()
     del X, U, Z
     torch.cuda.empty_cache()
