@@ -120,28 +120,27 @@ def main():
     k = 0
     last = None
 
-    def one_step(k, ev=None):
-        if ev:
-            ev[0].record(stream)
+    def one_step(k):
         eng.step(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
-        if ev:
-            ev[1].record(stream)
         return eng.consensus_stats(Z, W) if do_stats else None
 
     for _ in range(args.warmup):
         last = one_step(k)
         k += 1
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+    # HIP events around the step kernel, recorded by the library on the stream it launches on
+    eng.set_kernel_timing(True)
+    kern_ms = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        last = one_step(k, events[i])
+        last = one_step(k)
         k += 1
+        if i % 32 == 31:
+            kern_ms += eng.step_kernel_times()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-
-    kern_ms = [a.elapsed_time(b) for a, b in events]
+    kern_ms += eng.step_kernel_times()
+    assert len(kern_ms) == args.steps, (len(kern_ms), args.steps)
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
     bpu = algorithmic_bytes_per_update(wl)
     achieved = bpu * n * d / avg_kern_s / 1e9

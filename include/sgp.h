@@ -152,6 +152,18 @@ const char *sgp_status_string(int status);
 /* hipError_t value of the last failed HIP call on this handle (0 if none). */
 int sgp_last_hip_error(const sgp_handle *h);
 
+/*
+ * Measurement utility.  With timing enabled, sgp_step brackets its fused step kernel (not the
+ * single-block weight kernel in front of it) with HIP events recorded on the stream the kernel is
+ * launched on; the library keeps the last SGP_TIMING_RING pairs.
+ * sgp_step_kernel_times waits for the most recent timed kernel, writes the durations (ms, oldest
+ * first) of the timed steps since the previous call into ms_out[0 .. max-1] and their number into
+ * *count (at most min(max, SGP_TIMING_RING); older ones are dropped).
+ */
+#define SGP_TIMING_RING 64
+int sgp_set_kernel_timing(sgp_handle *h, int enable);
+int sgp_step_kernel_times(sgp_handle *h, float *ms_out, int32_t max, int32_t *count);
+
 /* Measurement utility: plain 128-bit streaming copy of nbytes (multiple of 16, both pointers
  * 16-byte aligned, device memory) on `stream`.  Serves as the known-size reference when
  * hardware traffic counters are scaled, and as the practical bandwidth ceiling of the part. */

@@ -26,7 +26,7 @@ SGP_TOPO_DIRECTED_EXP = 0
 # every symbol include/sgp.h declares
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
-           "sgp_last_hip_error", "sgp_copy")
+           "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times")
 
 
 class SgpError(RuntimeError):
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_status_string.restype = ctypes.c_char_p
     lib.sgp_last_hip_error.argtypes = [vp]
     lib.sgp_copy.argtypes = [vp, vp, i64, vp]
+    lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
+    lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
         if name != "sgp_status_string":
             getattr(lib, name).restype = ctypes.c_int
@@ -194,6 +196,18 @@ class SGP:
                                            ctypes.byref(wt)), "sgp_peer_schedule")
         rows = lambda a: [list(a[i * peers:(i + 1) * peers]) for i in range(n)]
         return rows(out), rows(inp), wt.value
+
+    def set_kernel_timing(self, enable: bool) -> None:
+        _check(self._lib.sgp_set_kernel_timing(self._h, int(enable)), "sgp_set_kernel_timing")
+
+    def step_kernel_times(self):
+        """Durations (ms) of the step kernels timed since the last call (at most 64, oldest first);
+        waits for the latest one."""
+        buf = (ctypes.c_float * 64)()
+        cnt = ctypes.c_int32()
+        _check(self._lib.sgp_step_kernel_times(self._h, ctypes.addressof(buf), 64, ctypes.byref(cnt)),
+               "sgp_step_kernel_times")
+        return list(buf[:cnt.value])
 
     def reset(self) -> None:
         _check(self._lib.sgp_reset(self._h), "sgp_reset")

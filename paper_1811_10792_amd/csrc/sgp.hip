@@ -648,23 +648,26 @@ __global__ __launch_bounds__(kBlock) void k_stats_large(const float *__restrict_
     }
 }
 
-// Final reduction: out[0..6] = max, mean, min, sum w, ||zbar||, argmax, argmin; out[8+i] = dist_i.
-constexpr int kFinalBlock = 1024;
-__global__ __launch_bounds__(kFinalBlock) void k_stats_final(const float *__restrict__ partial, int G,
-                                                            int n, const float *__restrict__ w,
-                                                            double *__restrict__ out)
+// Final reduction, step 1: block r adds up row r of the partial table in double.
+constexpr int kRowSumBlock = 256;
+__global__ __launch_bounds__(kRowSumBlock) void k_stats_rowsum(const float *__restrict__ partial, int G,
+                                                              double *__restrict__ sums)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
-    double *sums = reinterpret_cast<double *>(smem);       // [n+1]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int row = wave; row <= n; row += kFinalBlock / 64) {
-        double s = 0.0;
-        for (int b = lane; b < G; b += 64) s += (double)partial[(size_t)row * G + b];
-        s = wave_sum(s);
-        if (lane == 0) sums[row] = s;
-    }
+    const float *row = partial + (size_t)blockIdx.x * G;
+    double s = 0.0;
+    for (int b = threadIdx.x; b < G; b += kRowSumBlock) s += (double)row[b];
+    s = wave_sum(s);
+    __shared__ double red[kRowSumBlock / 64];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += kFinalBlock) out[8 + i] = sqrt(sums[i]);
+    if (threadIdx.x == 0) sums[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Step 2: out[0..6] = max, mean, min, sum w, ||zbar||, argmax, argmin; out[8+i] = dist_i.
+__global__ void k_stats_final(const double *__restrict__ sums, int n, const float *__restrict__ w,
+                              double *__restrict__ out)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x) out[8 + i] = sqrt(sums[i]);
     if (threadIdx.x == 0) {
         double dmax = 0.0, dmin = 0.0, dsum = 0.0, wsum = 0.0;
         int amax = 0, amin = 0;
@@ -711,6 +714,7 @@ struct sgp_handle {
     int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
     int G;
+    double *d_sums;     // [n+1] per-node sums of squares (+ the average's)
     double *d_result;   // [8 + n]
     double *h_result;   // pinned mirror
     float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
@@ -719,6 +723,12 @@ struct sgp_handle {
     bool have_msgs;
     int64_t last_k;
     int last_hip;
+
+    bool timing;                          // bracket the step kernel with events
+    hipEvent_t ev[SGP_TIMING_RING][2];
+    bool ev_made;
+    int64_t ev_head;                      // timed steps recorded so far
+    int64_t ev_read;                      // timed steps already reported
 };
 
 namespace {
@@ -777,6 +787,7 @@ int ensure_device(sgp_handle *h)
     h->G = kStatsGridMax;
     e = hipMalloc(&h->d_unit_w, sizeof(int));
     if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(&h->d_sums, (size_t)(n + 1) * sizeof(double));
     if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)(8 + n) * sizeof(double));
     if (e == hipSuccess)
         e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)(8 + n) * sizeof(double),
@@ -795,9 +806,15 @@ int ensure_device(sgp_handle *h)
 
 void release_device(sgp_handle *h)
 {
+    if (h->ev_made)
+        for (int i = 0; i < SGP_TIMING_RING; ++i) {
+            (void)hipEventDestroy(h->ev[i][0]);
+            (void)hipEventDestroy(h->ev[i][1]);
+        }
     if (h->d_tab) (void)hipFree(h->d_tab);
     if (h->d_unit_w) (void)hipFree(h->d_unit_w);
     if (h->d_partial) (void)hipFree(h->d_partial);
+    if (h->d_sums) (void)hipFree(h->d_sums);
     if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
     for (int b = 0; b < 2; ++b) {
@@ -1000,9 +1017,22 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
 
+    hipEvent_t *tev = nullptr;
+    if (h->timing) {
+        if (!h->ev_made) {
+            for (int i = 0; i < SGP_TIMING_RING; ++i) {
+                SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][0]));
+                SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][1]));
+            }
+            h->ev_made = true;
+        }
+        tev = h->ev[h->ev_head % SGP_TIMING_RING];
+    }
+
     if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
         hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w);
+        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         if (!gather) {
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
@@ -1026,6 +1056,7 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
         const int cur = h->cur, prv = cur ^ 1;
         hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
                            n, tab_prev, S, s.p, h->d_unit_w);
+        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0)
                 launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S);
@@ -1036,7 +1067,36 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
         h->have_msgs = true;
         h->last_k = k;
     }
+    if (tev) {
+        SGP_HIP_TRY(h, hipEventRecord(tev[1], st));
+        ++h->ev_head;
+    }
     SGP_HIP_TRY(h, hipGetLastError());
+    return SGP_OK;
+}
+
+int sgp_set_kernel_timing(sgp_handle *h, int enable)
+{
+    if (!h) return SGP_ERR_INVALID_ARG;
+    h->timing = enable != 0;
+    h->ev_read = h->ev_head;
+    return SGP_OK;
+}
+
+int sgp_step_kernel_times(sgp_handle *h, float *ms_out, int32_t max, int32_t *count)
+{
+    if (!h || !ms_out || !count || max < 0) return SGP_ERR_INVALID_ARG;
+    *count = 0;
+    int64_t first = h->ev_read;
+    if (h->ev_head - first > SGP_TIMING_RING) first = h->ev_head - SGP_TIMING_RING;
+    if (h->ev_head - first > max) first = h->ev_head - max;
+    if (h->ev_head == first) return SGP_OK;
+    SGP_HIP_TRY(h, hipEventSynchronize(h->ev[(h->ev_head - 1) % SGP_TIMING_RING][1]));
+    for (int64_t i = first; i < h->ev_head; ++i) {
+        hipEvent_t *e = h->ev[i % SGP_TIMING_RING];
+        SGP_HIP_TRY(h, hipEventElapsedTime(&ms_out[(*count)++], e[0], e[1]));
+    }
+    h->ev_read = h->ev_head;
     return SGP_OK;
 }
 
@@ -1091,8 +1151,8 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
     };
     if (cols4 > 0) run(std::integral_constant<int, 4>{}, 0, cols4);
     if (tail > 0) run(std::integral_constant<int, 1>{}, tail0, tail);
-    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(kFinalBlock), (size_t)(n + 1) * sizeof(double), st,
-                       h->d_partial, G, n, w, h->d_result);
+    hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, h->d_partial, G, h->d_sums);
+    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
     SGP_HIP_TRY(h, hipGetLastError());
     SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
                                   hipMemcpyDeviceToHost, st));
