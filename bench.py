@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the library's plain copy kernel over one state array (a transfer of "
+                         "known size, against which hardware traffic counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all simulated nodes live in one HBM); "
@@ -127,6 +130,9 @@ def main():
     for _ in range(args.warmup):
         last = one_step(k)
         k += 1
+    if args.calibrate_copy:
+        sgp.sgp_copy(Z, pool[0])          # n*ld*4 bytes read, n*ld*4 bytes written
+        torch.cuda.synchronize()
     # HIP events around the step kernel, recorded by the library on the stream it launches on
     eng.set_kernel_timing(True)
     kern_ms = []
