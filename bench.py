@@ -94,6 +94,10 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    ap.add_argument("--placement", choices=("regions", "default"), default="regions",
+                    help="regions: carve the state arrays out of one arena so that the written "
+                         "streams x, u, z sit in different HBM regions (found by timing); "
+                         "default: plain allocations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel over one state array (a transfer of "
                          "known size, against which hardware traffic counters are scaled)")
@@ -105,18 +109,23 @@ def main():
     import torch
     import paper_1811_10792_amd as sgp
     from paper_1811_10792_amd import synthetic as syn
+    from paper_1811_10792_amd.placement import StateAllocator
 
     wl = syn.WORKLOADS[args.workload]
     n, d = wl.n, wl.d
     torch.cuda.set_device(0)
     nest = wl.momentum != 0.0
     ld = syn.padded_ld(d)                 # rows start on 1 KiB boundaries
+    alloc = StateAllocator(args.placement)
     eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
-    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3)
-    U = torch.zeros_like(X)
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3, out=alloc.floats("x", n, ld))
+    U = alloc.floats("u", n, ld).zero_()
     W = torch.ones(n, dtype=torch.float32, device="cuda")
-    Z = torch.empty_like(X)
-    pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i) for i in range(max(1, args.pool))]
+    Z = alloc.floats("z", n, ld)
+    pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i, out=alloc.floats("g", n, ld, "g%d" % i))
+            for i in range(max(1, args.pool))]
+    if wl.delay:
+        eng.set_message_buffers(alloc.floats("msg0", n, ld), alloc.floats("msg1", n, ld))
     do_stats = wl.stats_each_step and not args.no_stats
     stream = torch.cuda.current_stream()
 
@@ -160,7 +169,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "peers": wl.peers, "delay": wl.delay,
                    "momentum": wl.momentum, "gamma": wl.gamma,
-                   "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool)},
+                   "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool),
+                   "placement": alloc.describe()},
         "roofline": {"bound": "hbm", "kernel": "fused sgp_step kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
@@ -170,7 +180,7 @@ def main():
     if last is not None:
         out["consensus_dist_max_last"] = last.dist_max
     eng.close()
-    del X, U, Z, pool
+    del X, U, Z, pool, alloc
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

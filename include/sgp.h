@@ -88,6 +88,14 @@ int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topol
  * Synchronises the device first.  NULL is accepted. */
 int sgp_destroy(sgp_handle *h);
 
+/* Overlap mode: makes the library keep its two message buffers in caller-owned device memory
+ * (each [n][ld] floats, 16-byte aligned, distinct, not overlapping any state array) instead of
+ * allocating them, e.g. so that the caller controls where in HBM they live.  Must be called
+ * before the first sgp_step on the handle; also drops messages in flight like sgp_reset.
+ * Errors: SGP_ERR_INVALID_ARG (null, equal or misaligned pointers, delay == 0),
+ * SGP_ERR_SEQUENCE (device resources already set up). */
+int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1);
+
 /* Overlap mode: drops the messages in flight, so that the next sgp_step receives nothing (as
  * the first iteration of Alg. 2 does) and may start at any k.  No-op for delay == 0. */
 int sgp_reset(sgp_handle *h);

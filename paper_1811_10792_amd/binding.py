@@ -26,7 +26,8 @@ SGP_TOPO_DIRECTED_EXP = 0
 # every symbol include/sgp.h declares
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
-           "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times")
+           "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
+           "sgp_set_message_buffers")
 
 
 class SgpError(RuntimeError):
@@ -80,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_status_string.restype = ctypes.c_char_p
     lib.sgp_last_hip_error.argtypes = [vp]
     lib.sgp_copy.argtypes = [vp, vp, i64, vp]
+    lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -196,6 +198,14 @@ class SGP:
                                            ctypes.byref(wt)), "sgp_peer_schedule")
         rows = lambda a: [list(a[i * peers:(i + 1) * peers]) for i in range(n)]
         return rows(out), rows(inp), wt.value
+
+    def set_message_buffers(self, buf0, buf1) -> None:
+        """Overlap mode: keep the two message buffers in these caller-owned [n, ld] tensors."""
+        self._expect(buf0, "buf0")
+        self._expect(buf1, "buf1")
+        self._msg_keepalive = (buf0, buf1)
+        _check(self._lib.sgp_set_message_buffers(self._h, _ptr(buf0), _ptr(buf1)),
+               "sgp_set_message_buffers")
 
     def set_kernel_timing(self, enable: bool) -> None:
         _check(self._lib.sgp_set_kernel_timing(self._h, int(enable)), "sgp_set_kernel_timing")

@@ -388,10 +388,22 @@ __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
 // Fused step of 1-overlap SGP (Alg. 2, tau = 1).  Node i keeps its own share p*xh_i (which is
 // also the message it sends: uniform weights), and then adds the messages that its in-neighbours
 // of the PREVIOUS iteration sent, in ascending sender index.  msg_prev/msg_cur are [n][ld]
-// buffers of pre-weighted messages p*xh_j.  tab_prev lists the previous iteration's sources
-// (self included, skipped here); NULL when nothing has been sent yet.
-// NM = number of messages per node known at compile time (0, 1, 2) or -1 for "read S at run time".
+// buffers of pre-weighted messages p*xh_j.  tab_prev lists the previous iteration's sources of
+// every node, sorted, the node itself included exactly once (skipped here); NULL when nothing
+// has been sent yet.  There is no dependency between nodes inside an iteration, so the nodes are
+// simply visited in order, software-pipelined like the one-peer walk.
+// NM = messages per node known at compile time (0, 1, 2), or -1: read S at run time and fetch the
+// messages while summing.
 // ------------------------------------------------------------------------------------------
+constexpr int kDelayCols = 2;   // 128-bit column groups per work-item
+
+template <int V, bool NEST, int C, int M>
+struct DelayRegs {
+    typename vec_of<V>::type x[C], u[C], g[C], m[M > 0 ? M : 1][C];
+    float w;
+    int node;
+};
+
 template <int V, bool NEST, bool ZOUT, int NM, bool DIV>
 __device__ __forceinline__ void delay_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
@@ -400,59 +412,80 @@ __device__ __forceinline__ void delay_body(
     const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
 {
     typedef typename vec_of<V>::type T;
-    constexpr int M = NM > 0 ? NM : 1;
-    long c = (long)blockIdx.x * kBlock + threadIdx.x;
-    if (c >= ncols) return;
-    const size_t off = col0 + (size_t)c * V;
+    constexpr int C = kDelayCols;
+    constexpr int M = NM > 0 ? NM : 0;
+    const long cbase = (long)blockIdx.x * (kBlock * C) + threadIdx.x;
+    size_t off[C];
+    bool live[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        long c = cbase + (long)j * kBlock;
+        live[j] = c < ncols;
+        off[j] = col0 + (size_t)(live[j] ? c : 0) * V;
+    }
+    if (!live[0]) return;
 
-    for (int i0 = 0; i0 < n; i0 += kBatch) {
-        T xv[kBatch], uv[kBatch], gv[kBatch], mv[kBatch][M];
+    auto load_row = [&](DelayRegs<V, NEST, C, M> &r, int node) {
+        r.node = node;
+        r.w = (ZOUT && DIV) ? w[node] : 1.0f;
+        const size_t row = (size_t)node * ld;
 #pragma unroll
-        for (int q = 0; q < kBatch; ++q) {
-            if (i0 + q < n) {
-                int i = i0 + q;
-                size_t a = (size_t)i * ld + off;
-                xv[q] = ld_stream<V>(x + a);
-                if (NEST) uv[q] = ld_stream<V>(u + a);
-                gv[q] = ld_stream<V>(g + a);
-                if (NM > 0) {
-                    // sources are sorted and contain i itself exactly once: drop it, keep order
-                    const int *src = tab_prev + (size_t)i * S;
-                    int taken = 0;
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                r.x[j] = ld_stream<V>(x + row + off[j]);
+                if (NEST) r.u[j] = ld_stream<V>(u + row + off[j]);
+                r.g[j] = ld_stream<V>(g + row + off[j]);
+            }
+        if (M > 0) {
+            // the sorted list holds `node` once, at position ps; message s is entry s + (s >= ps)
+            const int *src = tab_prev + (size_t)node * (M + 1);
+            int ps = 0;
 #pragma unroll
-                    for (int s = 0; s < M + 1; ++s) {
-                        int j = src[s];
-                        if (j != i && taken < M) {
-                            mv[q][taken] = ld_cached<V>(msg_prev + (size_t)j * ld + off);
-                            ++taken;
-                        }
-                    }
-                }
+            for (int e = 0; e < M + 1; ++e) ps += (src[e] < node) ? 1 : 0;
+#pragma unroll
+            for (int sidx = 0; sidx < M; ++sidx) {
+                const int sender = src[sidx + (sidx >= ps ? 1 : 0)];
+                const size_t mrow = (size_t)sender * ld;
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    if (live[j]) r.m[sidx][j] = ld_cached<V>(msg_prev + mrow + off[j]);
             }
         }
+    };
+
+    auto process_row = [&](const DelayRegs<V, NEST, C, M> &r) {
+        const size_t row = (size_t)r.node * ld;
 #pragma unroll
-        for (int q = 0; q < kBatch; ++q) {
-            if (i0 + q < n) {
-                int i = i0 + q;
-                size_t a = (size_t)i * ld + off;
-                T xh = half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                const size_t a = row + off[j];
+                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom, u + a);
                 T own = p * xh;
                 st_stream<V>(msg_cur + a, own);
                 T acc = own;
                 if (NM > 0) {
 #pragma unroll
-                    for (int s = 0; s < M; ++s) acc = acc + mv[q][s];
+                    for (int sidx = 0; sidx < M; ++sidx) acc = acc + r.m[sidx][j];
                 } else if (NM < 0) {
-                    const int *src = tab_prev + (size_t)i * S;
-                    for (int s = 0; s < S; ++s) {
-                        int j = src[s];
-                        if (j != i) acc = acc + ld_cached<V>(msg_prev + (size_t)j * ld + off);
+                    const int *src = tab_prev + (size_t)r.node * S;
+                    for (int e = 0; e < S; ++e) {
+                        const int sender = src[e];
+                        if (sender != r.node)
+                            acc = acc + ld_cached<V>(msg_prev + (size_t)sender * ld + off[j]);
                     }
                 }
                 st_stream<V>(x + a, acc);
-                if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(acc, DIV ? w[i] : 1.0f));
+                if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(acc, r.w));
             }
-        }
+    };
+
+    DelayRegs<V, NEST, C, M> ra, rb;
+    load_row(ra, 0);
+    for (int t = 0; t < n; t += 2) {
+        if (t + 1 < n) load_row(rb, t + 1);
+        process_row(ra);
+        if (t + 2 < n) load_row(ra, t + 2);
+        if (t + 1 < n) process_row(rb);
     }
 }
 
@@ -718,6 +751,7 @@ struct sgp_handle {
     double *d_result;   // [8 + n]
     double *h_result;   // pinned mirror
     float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
+    bool msg_external;  // d_msg points into caller-owned memory
     float *d_msgw[2];   // overlap mode: pre-weighted weights p*w_j, [n] each
     int cur;            // buffer that the NEXT step writes
     bool have_msgs;
@@ -795,7 +829,7 @@ int ensure_device(sgp_handle *h)
     if (e == hipSuccess && h->delay) {
         size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
         for (int b = 0; b < 2 && e == hipSuccess; ++b) {
-            e = hipMalloc(&h->d_msg[b], bytes);
+            if (!h->msg_external) e = hipMalloc(&h->d_msg[b], bytes);
             if (e == hipSuccess) e = hipMalloc(&h->d_msgw[b], (size_t)n * sizeof(float));
         }
     }
@@ -818,7 +852,7 @@ void release_device(sgp_handle *h)
     if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
     for (int b = 0; b < 2; ++b) {
-        if (h->d_msg[b]) (void)hipFree(h->d_msg[b]);
+        if (h->d_msg[b] && !h->msg_external) (void)hipFree(h->d_msg[b]);
         if (h->d_msgw[b]) (void)hipFree(h->d_msgw[b]);
     }
 }
@@ -857,7 +891,7 @@ template <int V, bool NEST, bool ZOUT>
 void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
                   const int *tab_prev, int S)
 {
-    dim3 grid(grid_for(ncols, kBlock)), block(kBlock);
+    dim3 grid(grid_for(ncols, kBlock * kDelayCols)), block(kBlock);
     const int nm = tab_prev ? S - 1 : 0;
     if (nm == 0)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
@@ -954,6 +988,19 @@ int sgp_destroy(sgp_handle *h)
 int sgp_reset(sgp_handle *h)
 {
     if (!h) return SGP_ERR_INVALID_ARG;
+    h->have_msgs = false;
+    h->last_k = -1;
+    return SGP_OK;
+}
+
+int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1)
+{
+    if (!h || !buf0 || !buf1 || buf0 == buf1 || !h->delay || !aligned16(buf0) || !aligned16(buf1))
+        return SGP_ERR_INVALID_ARG;
+    if (h->dev_ready) return SGP_ERR_SEQUENCE;
+    h->d_msg[0] = buf0;
+    h->d_msg[1] = buf1;
+    h->msg_external = true;
     h->have_msgs = false;
     h->last_k = -1;
     return SGP_OK;

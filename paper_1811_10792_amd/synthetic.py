@@ -101,13 +101,15 @@ def initial_state(wl: Workload):
 
 # ---- device-side generators for the model-sized workloads (torch used for memory only) -------
 
-def device_normal(n: int, ld: int, std: float, seed: int, stream: int, device="cuda"):
+def device_normal(n: int, ld: int, std: float, seed: int, stream: int, device="cuda", out=None):
     """float32 [n, ld] N(0, std) tensor drawn on the device from a seeded generator (padding
-    columns, if ld exceeds d, are drawn too; the library never touches them)."""
+    columns, if ld exceeds d, are drawn too; the library never touches them).  With `out`, the
+    draw goes into that tensor (same values as a fresh one: the generator only sees the count)."""
     import torch
-    gen = torch.Generator(device=device)
+    if out is None:
+        out = torch.empty((n, ld), dtype=torch.float32, device=device)
+    gen = torch.Generator(device=out.device)
     gen.manual_seed((int(seed) * 1_000_003 + int(stream)) & 0x7FFFFFFFFFFFFFFF)
-    out = torch.empty((n, ld), dtype=torch.float32, device=device)
     out.normal_(0.0, float(std), generator=gen)
     return out
 

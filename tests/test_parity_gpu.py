@@ -280,26 +280,57 @@ def test_exact_averaging_on_device():
 
 
 # ------------------------------------------------------------------- full-size spot checks
+_ALLOC = None
+
+
+def _bench_allocator():
+    """The benchmark's region-aware allocator, set up once for the full-size tests."""
+    global _ALLOC
+    if _ALLOC is None:
+        from paper_1811_10792_amd.placement import StateAllocator
+        torch.cuda.empty_cache()
+        _ALLOC = StateAllocator("regions")
+    return _ALLOC
+
+
+def test_placement_probe_finds_regions_and_separates_the_written_streams():
+    alloc = _bench_allocator()
+    info = alloc.describe()
+    assert info["mode"] == "regions"
+    t = {r: alloc.floats(r, 4, 1 << 20) for r in ("x", "u", "z", "g")}
+    info = alloc.describe()
+    if info["structured"]:                       # three written streams in three different regions
+        assert len({info["arrays"][r] for r in ("x", "u", "z")}) == 3
+    ptrs = sorted((v.data_ptr(), v.numel() * 4) for v in t.values())
+    assert all(a + n <= b for (a, n), (b, _) in zip(ptrs, ptrs[1:]))     # disjoint
+    assert all(p % 4096 == 0 for p, _ in ptrs)
+    alloc.reset()
+
+
 def _full_size_spot_check(wl, steps, count=3000):
     """Model-sized state generated on the device, the launch configuration the benchmark times;
     the oracle recomputes a sample of coordinates (coordinates are independent, so a column
     slice of the oracle is exact), including the first tile and the ragged tail."""
     n, d = wl.n, wl.d
     ld = syn.padded_ld(d)                                      # the benchmark's row stride
-    torch.cuda.empty_cache()
-    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3)
-    U = syn.device_normal(n, ld, wl.grad_std, wl.seed, 6)     # a non-trivial momentum buffer
+    alloc = _bench_allocator()                                 # and its placement of the arrays
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3, out=alloc.floats("x", n, ld))
+    U = syn.device_normal(n, ld, wl.grad_std, wl.seed, 6,     # a non-trivial momentum buffer
+                          out=alloc.floats("u", n, ld))
     W = torch.ones(n, dtype=torch.float32, device=DEV)
-    Z = torch.empty_like(X)
+    Z = alloc.floats("z", n, ld)
+    Gbuf = alloc.floats("g", n, ld)
     cols = syn.sample_columns(d, count, wl.seed)
     cidx = torch.from_numpy(cols).to(DEV)
     xo, uo = host(X[:, cidx]), host(U[:, cidx])
     wo = np.ones(n, np.float32)
     eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
+    if wl.delay:
+        eng.set_message_buffers(alloc.floats("msg0", n, ld), alloc.floats("msg1", n, ld))
     st = O.Delay1State(n, len(cols), np.float32) if wl.delay else None
     pad0 = [host(T[:, d:]).copy() for T in (X, U)]
     for k in range(steps):
-        G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + k)
+        G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + k, out=Gbuf)
         g = host(G[:, cidx])
         eng.step(X, W, U, G, Z, wl.gamma, wl.momentum, k)
         P = O.mixing_matrix(n, wl.peers, k, np.float32)
@@ -311,7 +342,6 @@ def _full_size_spot_check(wl, steps, count=3000):
         same(host(Z[:, cidx]), zo, "%s z k=%d" % (wl.name, k))
         same(host(U[:, cidx]), uo, "%s u k=%d" % (wl.name, k))
         same(host(W), wo, "%s w k=%d" % (wl.name, k))
-        del G
     if wl.stats_each_step:
         # statistics are sums over coordinates: check them on a contiguous slice the oracle can
         # afford, through the same entry point, and the full-size call for sanity
@@ -327,8 +357,8 @@ def _full_size_spot_check(wl, steps, count=3000):
     for T, p0 in zip((X, U), pad0):                            # padding columns stay untouched
         assert np.array_equal(host(T[:, d:]), p0)
     eng.close()
-    del X, U, Z
-    torch.cuda.empty_cache()
+    del X, U, Z, G, Gbuf
+    alloc.reset()
 
 
 def test_full_size_config3_n16_resnet50():
