@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    ap.add_argument("--separate-stats", action="store_true",
+                    help="run sgp_step and sgp_consensus_stats as two calls instead of sgp_step_stats")
     ap.add_argument("--placement", choices=("regions", "default"), default="regions",
                     help="regions: carve the state arrays out of one arena so that the written "
                          "streams x, u, z sit in different HBM regions (found by timing); "
@@ -133,6 +135,9 @@ def main():
     last = None
 
     def one_step(k):
+        if do_stats and not args.separate_stats:    # one call: statistics fused into the step kernel
+            return eng.step_stats(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma,
+                                  wl.momentum, k)
         eng.step(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
         return eng.consensus_stats(Z, W) if do_stats else None
 

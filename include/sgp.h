@@ -137,6 +137,19 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
                         double *per_node_dist_host, void *stream);
 
 /*
+ * sgp_step followed by sgp_consensus_stats of the z^(k+1) it wrote, in one call (Alg. 1 / Alg. 3
+ * plus the "Parameter deviations" statistics).  Arguments as in those two calls; z_out and
+ * host_out are required.  For one out-peer without delay, n <= 32, d % 4 == 0 and the 128-bit
+ * layout, the statistics are accumulated inside the step kernel while z is still in registers
+ * (z is not read back from HBM); otherwise the two kernels run one after the other.  The state
+ * written is identical to sgp_step's; the statistics agree with sgp_consensus_stats to rounding
+ * (a different reference row is subtracted before squaring).  SYNCHRONISES the stream.
+ */
+int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+                   float gamma, float momentum, int64_t k, sgp_stats *host_out,
+                   double *per_node_dist_host, void *stream);
+
+/*
  * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).
  *   out_peers [n][peers] : out_peers[i*peers + r] = node that i sends to over its r-th hop,
  *                          (i + 2^((k+r) mod L)) mod n, or -1 if that peer repeats an earlier one

@@ -27,7 +27,7 @@ SGP_TOPO_DIRECTED_EXP = 0
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
-           "sgp_set_message_buffers")
+           "sgp_set_message_buffers", "sgp_step_stats")
 
 
 class SgpError(RuntimeError):
@@ -82,6 +82,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_last_hip_error.argtypes = [vp]
     lib.sgp_copy.argtypes = [vp, vp, i64, vp]
     lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
+    lib.sgp_step_stats.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -170,6 +171,21 @@ class SGP:
         self._expect(w, "w", rows_only=True)
         _check(self._lib.sgp_step(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), _ptr(z_out),
                                   gamma, momentum, k, _stream(stream)), "sgp_step")
+
+    def step_stats(self, x, w, m, g, z_out, gamma: float, momentum: float, k: int,
+                   per_node: bool = False, stream=None) -> Stats:
+        """One iteration plus the consensus statistics of the z it wrote (fused where possible)."""
+        for t, name in ((x, "x"), (m, "m"), (g, "g"), (z_out, "z_out")):
+            self._expect(t, name)
+        self._expect(w, "w", rows_only=True)
+        cs = _CStats()
+        buf = (ctypes.c_double * self.n)() if per_node else None
+        _check(self._lib.sgp_step_stats(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), _ptr(z_out),
+                                        gamma, momentum, k, ctypes.byref(cs),
+                                        ctypes.addressof(buf) if per_node else None,
+                                        _stream(stream)), "sgp_step_stats")
+        return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
+                     cs.argmin, list(buf) if per_node else None)
 
     def debias(self, x, w, z, stream=None) -> None:
         self._expect(x, "x")

@@ -577,6 +577,8 @@ __global__ __launch_bounds__(kBlock) void k_debias(const float *__restrict__ x,
 // ------------------------------------------------------------------------------------------
 constexpr int kStatsCache = 32;   // nodes whose z the small-n kernel keeps in registers
 
+#include "step_stats_kernel.inc"
+
 template <int V>
 __global__ __launch_bounds__(kBlock) void k_stats_small(const float *__restrict__ z, int n,
                                                        size_t ld, size_t col0, long ncols,
@@ -682,18 +684,28 @@ __global__ __launch_bounds__(kBlock) void k_stats_large(const float *__restrict_
 }
 
 // Final reduction, step 1: block r adds up row r of the partial table in double.
-constexpr int kRowSumBlock = 256;
+constexpr int kRowSumBlock = 1024;
 __global__ __launch_bounds__(kRowSumBlock) void k_stats_rowsum(const float *__restrict__ partial, int G,
                                                               double *__restrict__ sums)
 {
     const float *row = partial + (size_t)blockIdx.x * G;
-    double s = 0.0;
-    for (int b = threadIdx.x; b < G; b += kRowSumBlock) s += (double)row[b];
-    s = wave_sum(s);
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // independent chains: loads overlap
+    int b = threadIdx.x;
+    for (; b + 3 * kRowSumBlock < G; b += 4 * kRowSumBlock) {
+        const float v0 = row[b], v1 = row[b + kRowSumBlock], v2 = row[b + 2 * kRowSumBlock],
+                    v3 = row[b + 3 * kRowSumBlock];
+        s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
+    }
+    for (; b < G; b += kRowSumBlock) s0 += (double)row[b];
+    double s = wave_sum((s0 + s1) + (s2 + s3));
     __shared__ double red[kRowSumBlock / 64];
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
-    if (threadIdx.x == 0) sums[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) {
+        double tot = 0.0;
+        for (int i = 0; i < kRowSumBlock / 64; ++i) tot += red[i];
+        sums[blockIdx.x] = tot;
+    }
 }
 
 // Step 2: out[0..6] = max, mean, min, sum w, ||zbar||, argmax, argmin; out[8+i] = dist_i.
@@ -746,6 +758,8 @@ struct sgp_handle {
     int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
     int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
+    float *d_partial_f; // [(n+1)][Gf] partial sums written by the fused step+statistics kernel
+    size_t partial_f_elems;
     int G;
     double *d_sums;     // [n+1] per-node sums of squares (+ the average's)
     double *d_result;   // [8 + n]
@@ -848,6 +862,7 @@ void release_device(sgp_handle *h)
     if (h->d_tab) (void)hipFree(h->d_tab);
     if (h->d_unit_w) (void)hipFree(h->d_unit_w);
     if (h->d_partial) (void)hipFree(h->d_partial);
+    if (h->d_partial_f) (void)hipFree(h->d_partial_f);
     if (h->d_sums) (void)hipFree(h->d_sums);
     if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
@@ -1031,8 +1046,11 @@ int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_
     return sgp_schedule(h->n, h->peers, k, out_peers, in_peers, weight);
 }
 
-int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out, float gamma,
-             float momentum, int64_t k, void *stream)
+// One iteration; with fused_G != NULL the caller wants the statistics of z^(k+1) as well: when the
+// fused kernel applies, it is used and *fused_G receives the column count of h->d_partial_f,
+// otherwise *fused_G stays 0 and the caller runs the stand-alone statistics pass.
+static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+                     float gamma, float momentum, int64_t k, void *stream, int *fused_G)
 {
     if (!h || !x || !w || !g || k < 0) return SGP_ERR_INVALID_ARG;
     const bool nest = momentum != 0.0f;
@@ -1084,6 +1102,27 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
             const int len = n / ncyc;
+            if (fused_G && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
+                const unsigned Gf = grid_for(cols4, kStatsStepBlock);
+                const size_t need = (size_t)(n + 1) * Gf;
+                if (need > h->partial_f_elems) {
+                    if (h->d_partial_f) (void)hipFree(h->d_partial_f);
+                    h->d_partial_f = nullptr;
+                    h->partial_f_elems = 0;
+                    hipError_t e = hipMalloc(&h->d_partial_f, need * sizeof(float));
+                    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+                    h->partial_f_elems = need;
+                }
+                if (nest)
+                    hipLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
+                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, gamma,
+                                       momentum, h->d_partial_f);
+                else
+                    hipLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
+                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, gamma,
+                                       momentum, h->d_partial_f);
+                *fused_G = (int)Gf;
+            } else
             dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
                 if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, len);
                 if (tail > 0) launch_one_peer<1, NEST, ZOUT>(a, tail0, tail, hop, len);
@@ -1120,6 +1159,49 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
     }
     SGP_HIP_TRY(h, hipGetLastError());
     return SGP_OK;
+}
+
+int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out, float gamma,
+             float momentum, int64_t k, void *stream)
+{
+    return step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, nullptr);
+}
+
+// Reduces a partial table [(n+1)][G] to the statistics, copies them to the host and waits.
+static int finish_stats(sgp_handle *h, const float *partial, int G, const float *w, sgp_stats *host_out,
+                        double *per_node_dist_host, hipStream_t st)
+{
+    const int n = h->n;
+    hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);
+    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
+    SGP_HIP_TRY(h, hipGetLastError());
+    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
+                                  hipMemcpyDeviceToHost, st));
+    SGP_HIP_TRY(h, hipStreamSynchronize(st));
+    host_out->dist_max = h->h_result[0];
+    host_out->dist_mean = h->h_result[1];
+    host_out->dist_min = h->h_result[2];
+    host_out->w_sum = h->h_result[3];
+    host_out->zbar_norm = h->h_result[4];
+    host_out->argmax = (int32_t)h->h_result[5];
+    host_out->argmin = (int32_t)h->h_result[6];
+    if (per_node_dist_host)
+        for (int i = 0; i < n; ++i) per_node_dist_host[i] = h->h_result[8 + i];
+    return SGP_OK;
+}
+
+int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+                   float gamma, float momentum, int64_t k, sgp_stats *host_out,
+                   double *per_node_dist_host, void *stream)
+{
+    if (!z_out || !host_out) return SGP_ERR_INVALID_ARG;
+    int fused_G = 0;
+    int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused_G);
+    if (rc != SGP_OK) return rc;
+    if (fused_G > 0)
+        return finish_stats(h, h->d_partial_f, fused_G, w, host_out, per_node_dist_host,
+                            static_cast<hipStream_t>(stream));
+    return sgp_consensus_stats(h, z_out, w, host_out, per_node_dist_host, stream);
 }
 
 int sgp_set_kernel_timing(sgp_handle *h, int enable)
@@ -1198,22 +1280,8 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
     };
     if (cols4 > 0) run(std::integral_constant<int, 4>{}, 0, cols4);
     if (tail > 0) run(std::integral_constant<int, 1>{}, tail0, tail);
-    hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, h->d_partial, G, h->d_sums);
-    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
     SGP_HIP_TRY(h, hipGetLastError());
-    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
-                                  hipMemcpyDeviceToHost, st));
-    SGP_HIP_TRY(h, hipStreamSynchronize(st));
-    host_out->dist_max = h->h_result[0];
-    host_out->dist_mean = h->h_result[1];
-    host_out->dist_min = h->h_result[2];
-    host_out->w_sum = h->h_result[3];
-    host_out->zbar_norm = h->h_result[4];
-    host_out->argmax = (int32_t)h->h_result[5];
-    host_out->argmin = (int32_t)h->h_result[6];
-    if (per_node_dist_host)
-        for (int i = 0; i < n; ++i) per_node_dist_host[i] = h->h_result[8 + i];
-    return SGP_OK;
+    return finish_stats(h, h->d_partial, G, w, host_out, per_node_dist_host, st);
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
