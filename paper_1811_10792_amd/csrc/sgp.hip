@@ -26,6 +26,9 @@
 #ifndef SGP_OP_BLOCK
 #define SGP_OP_BLOCK 256
 #endif
+#ifndef SGP_OP_DYNLDS
+#define SGP_OP_DYNLDS 0   // unused dynamic LDS per block: an occupancy limiter for experiments
+#endif
 #ifndef SGP_OP_COLS
 #define SGP_OP_COLS 4
 #endif
@@ -709,8 +712,8 @@ __global__ __launch_bounds__(kRowSumBlock) void k_stats_rowsum(const float *__re
 }
 
 // Step 2: out[0..6] = max, mean, min, sum w, ||zbar||, argmax, argmin; out[8+i] = dist_i.
-__global__ void k_stats_final(const double *__restrict__ sums, int n, const float *__restrict__ w,
-                              double *__restrict__ out)
+__device__ __forceinline__ void stats_final_body(const double *sums, int n, const float *__restrict__ w,
+                                                 double *__restrict__ out)
 {
     for (int i = threadIdx.x; i < n; i += blockDim.x) out[8 + i] = sqrt(sums[i]);
     if (threadIdx.x == 0) {
@@ -732,6 +735,29 @@ __global__ void k_stats_final(const double *__restrict__ sums, int n, const floa
         out[6] = (double)amin;
         out[7] = 0.0;
     }
+}
+
+__global__ void k_stats_final(const double *__restrict__ sums, int n, const float *__restrict__ w,
+                              double *__restrict__ out)
+{
+    stats_final_body(sums, n, w, out);
+}
+
+// Step 2 after the fused kernel: adds the B block sums of k_stats_slotsum in block order and moves
+// every slot's sum to the node that the walk emitted into that slot.
+__global__ __launch_bounds__(64) void k_stats_final_slots(const double *__restrict__ sums2, int B, int n,
+                                                          int hop, int len, const float *__restrict__ w,
+                                                          double *__restrict__ out)
+{
+    __shared__ double sums[kStatsCache + 1];
+    const int s = threadIdx.x;
+    if (s < n || s == kStatsCache) {
+        double tot = 0.0;
+        for (int b = 0; b < B; ++b) tot += sums2[(size_t)b * (kStatsCache + 1) + s];
+        sums[s == kStatsCache ? n : stats_slot_node(s, n, hop, len)] = tot;
+    }
+    __syncthreads();
+    stats_final_body(sums, n, w, out);
 }
 
 __global__ __launch_bounds__(kBlock) void k_copy(floatx4 *__restrict__ dst,
@@ -761,7 +787,8 @@ struct sgp_handle {
     float *d_partial_f; // [(n+1)][Gf] partial sums written by the fused step+statistics kernel
     size_t partial_f_elems;
     int G;
-    double *d_sums;     // [n+1] per-node sums of squares (+ the average's)
+    double *d_sums;     // [n+1] per-node sums of squares (+ the average's), or the fused kernel's
+                        // [kSlotSumBlocks][33] block sums
     double *d_result;   // [8 + n]
     double *h_result;   // pinned mirror
     float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
@@ -835,7 +862,8 @@ int ensure_device(sgp_handle *h)
     h->G = kStatsGridMax;
     e = hipMalloc(&h->d_unit_w, sizeof(int));
     if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&h->d_sums, (size_t)(n + 1) * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(&h->d_sums,
+                                       (size_t)std::max(n + 1, kSlotSumBlocks * (kStatsCache + 1)) * sizeof(double));
     if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)(8 + n) * sizeof(double));
     if (e == hipSuccess)
         e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)(8 + n) * sizeof(double),
@@ -888,7 +916,7 @@ template <int V, bool NEST, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
     hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
-                       dim3(kOpBlock), 0,
+                       dim3(kOpBlock), SGP_OP_DYNLDS,
                        a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
                        len, a.p, a.gamma, a.mom);
 }
@@ -1046,11 +1074,17 @@ int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_
     return sgp_schedule(h->n, h->peers, k, out_peers, in_peers, weight);
 }
 
-// One iteration; with fused_G != NULL the caller wants the statistics of z^(k+1) as well: when the
-// fused kernel applies, it is used and *fused_G receives the column count of h->d_partial_f,
-// otherwise *fused_G stays 0 and the caller runs the stand-alone statistics pass.
+// What step_impl did about the statistics: G > 0 means the fused kernel ran and left its partial
+// table (G blocks) in h->d_partial_f for a walk with this hop and cycle length.
+struct FusedStats {
+    int G = 0, hop = 0, len = 1;
+};
+
+// One iteration; with fused != NULL the caller wants the statistics of z^(k+1) as well: when the
+// fused kernel applies, it is used and *fused describes the partial table it left in
+// h->d_partial_f, otherwise fused->G stays 0 and the caller runs the stand-alone statistics pass.
 static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
-                     float gamma, float momentum, int64_t k, void *stream, int *fused_G)
+                     float gamma, float momentum, int64_t k, void *stream, FusedStats *fused)
 {
     if (!h || !x || !w || !g || k < 0) return SGP_ERR_INVALID_ARG;
     const bool nest = momentum != 0.0f;
@@ -1102,9 +1136,9 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
             const int len = n / ncyc;
-            if (fused_G && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
+            if (fused && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
                 const unsigned Gf = grid_for(cols4, kStatsStepBlock);
-                const size_t need = (size_t)(n + 1) * Gf;
+                const size_t need = (size_t)(kStatsCache + 1) * Gf;
                 if (need > h->partial_f_elems) {
                     if (h->d_partial_f) (void)hipFree(h->d_partial_f);
                     h->d_partial_f = nullptr;
@@ -1121,7 +1155,9 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
                     hipLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
                                        z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, gamma,
                                        momentum, h->d_partial_f);
-                *fused_G = (int)Gf;
+                fused->G = (int)Gf;
+                fused->hop = hop;
+                fused->len = len;
             } else
             dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
                 if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, len);
@@ -1167,13 +1203,21 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
     return step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, nullptr);
 }
 
-// Reduces a partial table [(n+1)][G] to the statistics, copies them to the host and waits.
-static int finish_stats(sgp_handle *h, const float *partial, int G, const float *w, sgp_stats *host_out,
-                        double *per_node_dist_host, hipStream_t st)
+// Reduces a partial table to the statistics, copies them to the host and waits.  fused == NULL:
+// the stand-alone kernels' table [(n+1)][G]; else the fused kernel's.
+static int finish_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
+                        sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
 {
     const int n = h->n;
-    hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);
-    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
+    if (fused) {
+        const int B = std::min(kSlotSumBlocks, G);
+        hipLaunchKernelGGL(k_stats_slotsum, dim3(B), dim3(kSlotSumBlock), 0, st, partial, G, h->d_sums);
+        hipLaunchKernelGGL(k_stats_final_slots, dim3(1), dim3(64), 0, st, h->d_sums, B, n, fused->hop,
+                           fused->len, w, h->d_result);
+    } else {
+        hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);
+        hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
+    }
     SGP_HIP_TRY(h, hipGetLastError());
     SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
                                   hipMemcpyDeviceToHost, st));
@@ -1195,11 +1239,11 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
                    double *per_node_dist_host, void *stream)
 {
     if (!z_out || !host_out) return SGP_ERR_INVALID_ARG;
-    int fused_G = 0;
-    int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused_G);
+    FusedStats fused;
+    int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
     if (rc != SGP_OK) return rc;
-    if (fused_G > 0)
-        return finish_stats(h, h->d_partial_f, fused_G, w, host_out, per_node_dist_host,
+    if (fused.G > 0)
+        return finish_stats(h, h->d_partial_f, fused.G, &fused, w, host_out, per_node_dist_host,
                             static_cast<hipStream_t>(stream));
     return sgp_consensus_stats(h, z_out, w, host_out, per_node_dist_host, stream);
 }
@@ -1281,7 +1325,7 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
     if (cols4 > 0) run(std::integral_constant<int, 4>{}, 0, cols4);
     if (tail > 0) run(std::integral_constant<int, 1>{}, tail0, tail);
     SGP_HIP_TRY(h, hipGetLastError());
-    return finish_stats(h, h->d_partial, G, w, host_out, per_node_dist_host, st);
+    return finish_stats(h, h->d_partial, G, nullptr, w, host_out, per_node_dist_host, st);
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
