@@ -23,14 +23,16 @@
 #pragma clang fp contract(off)
 
 // Tuning knobs (overridable at build time for tuning runs).
+// One-peer step kernel: single-wave blocks, one 128-bit column group per work-item measured best
+// (n = 32, d = 25.6 M: 3.05 ms; 256 x 4: 3.07 ms; 256 x 2: 3.17 ms).
 #ifndef SGP_OP_BLOCK
-#define SGP_OP_BLOCK 256
+#define SGP_OP_BLOCK 64
 #endif
 #ifndef SGP_OP_DYNLDS
 #define SGP_OP_DYNLDS 0   // unused dynamic LDS per block: an occupancy limiter for experiments
 #endif
 #ifndef SGP_OP_COLS
-#define SGP_OP_COLS 4
+#define SGP_OP_COLS 1
 #endif
 #ifndef SGP_NT_LOAD
 #define SGP_NT_LOAD 1
@@ -211,7 +213,17 @@ struct WalkPos {
     }
 };
 
-template <int V, bool NEST, bool ZOUT, bool DIV>
+// What keeps the pipeline alive is that the compiler can count, at every wait, how many memory
+// operations were issued after the loads it waits for.  It can only do that when every path through
+// the code issues the same number, so:
+//  - every row of the walk issues the same stores: its own u, and x and z of exactly ONE node.  A
+//    node that opens a cycle cannot be finished before the cycle closes; its result is then parked
+//    and written by the next row (which opens the next cycle and has nothing of its own to write);
+//    the last parked node is written after the walk;
+//  - full blocks run an instantiation without per-lane predicates (MASKED = false);
+//  - the first row and the last one or two are peeled off, so that inside the loop the prefetch of
+//    the next row is unconditional.
+template <int V, bool NEST, bool ZOUT, bool DIV, bool MASKED>
 __device__ __forceinline__ void one_peer_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
@@ -225,10 +237,10 @@ __device__ __forceinline__ void one_peer_body(
 #pragma unroll
     for (int j = 0; j < C; ++j) {
         long c = cbase + (long)j * kOpBlock;
-        live[j] = c < ncols;
+        live[j] = !MASKED || c < ncols;
         off[j] = col0 + (size_t)(live[j] ? c : 0) * V;
     }
-    if (!live[0]) return;
+    if (MASKED && !live[0]) return;
 
     auto load_row = [&](RowRegs<V, NEST, C> &r, int node) {
         r.node = node;
@@ -243,72 +255,95 @@ __device__ __forceinline__ void one_peer_body(
             }
     };
 
-    T first[C], prev[C];
+    T first[C], prev[C], parked[C];
 #pragma unroll
-    for (int j = 0; j < C; ++j) first[j] = prev[j] = T(0);
-    int first_node = 0;
-    float first_w = 1.0f;
+    for (int j = 0; j < C; ++j) first[j] = prev[j] = parked[j] = T(0);
+    int first_node = 0, parked_node = 0;
+    float first_w = 1.0f, parked_w = 1.0f;
     int ppos = 0;   // position of the node being processed within its cycle
 
-    auto process_row = [&](const RowRegs<V, NEST, C> &r) {
-        const size_t row = (size_t)r.node * ld;
-        const bool opens = (ppos == 0), closes = (ppos == len - 1);
+    auto emit = [&](int node, float wi, const T (&xn)[C]) {
+        const size_t row = (size_t)node * ld;
 #pragma unroll
         for (int j = 0; j < C; ++j)
             if (live[j]) {
-                const size_t a = row + off[j];
-                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom, u + a);
-                if (opens) {
-                    first[j] = xh;
-                } else {
-                    T a0 = p * xh;
-                    T a1 = p * prev[j];
-                    T xn = a0 + a1;
-                    st_stream<V>(x + a, xn);
-                    if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(xn, r.w));
-                }
-                prev[j] = xh;
+                st_stream<V>(x + row + off[j], xn[j]);
+                if (ZOUT) st_stream<V>(z + row + off[j], debias_val<V, DIV>(xn[j], wi));
             }
+    };
+
+    // EMIT = false only for the very first row, which opens the first cycle with nothing parked.
+    auto process_row = [&]<bool EMIT>(const RowRegs<V, NEST, C> &r) {
+        const size_t row = (size_t)r.node * ld;
+        const bool opens = (ppos == 0), closes = (ppos == len - 1);
+        T xn[C];
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            T xh = T(0);
+            if (live[j])
+                xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom,
+                                        u + row + off[j]);
+            if (opens) {
+                xn[j] = parked[j];
+                first[j] = xh;
+            } else {
+                T a0 = p * xh;
+                T a1 = p * prev[j];
+                xn[j] = a0 + a1;
+            }
+            prev[j] = xh;
+        }
+        const int out_node = opens ? parked_node : r.node;
+        const float out_w = opens ? parked_w : r.w;
         if (opens) {
             first_node = r.node;
             first_w = r.w;
         }
         if (closes) {   // the first node of the cycle hears from the last one visited
-            const size_t frow = (size_t)first_node * ld;
 #pragma unroll
-            for (int j = 0; j < C; ++j)
-                if (live[j]) {
-                    const size_t a = frow + off[j];
-                    T xn = p * first[j];
-                    if (len > 1) {
-                        T a1 = p * prev[j];
-                        xn = xn + a1;
-                    }
-                    st_stream<V>(x + a, xn);
-                    if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(xn, first_w));
+            for (int j = 0; j < C; ++j) {
+                T pk = p * first[j];
+                if (len > 1) {
+                    T a1 = p * prev[j];
+                    pk = pk + a1;
                 }
+                parked[j] = pk;
+            }
+            parked_node = first_node;
+            parked_w = first_w;
             ppos = 0;
         } else {
             ++ppos;
         }
+        if (EMIT) emit(out_node, out_w, xn);
     };
 
     WalkPos lp{0, 0, 0};
     RowRegs<V, NEST, C> ra, rb;
     load_row(ra, lp.node);
     lp.advance(n, h, len);
-    for (int t = 0; t < n; t += 2) {
-        if (t + 1 < n) {
-            load_row(rb, lp.node);
-            lp.advance(n, h, len);
-        }
-        process_row(ra);
-        if (t + 2 < n) {
-            load_row(ra, lp.node);
-            lp.advance(n, h, len);
-        }
-        if (t + 1 < n) process_row(rb);
+    if (n > 1) {
+        load_row(rb, lp.node);
+        lp.advance(n, h, len);
     }
+    process_row.template operator()<false>(ra);
+    int t = 1;                      // rb holds row t (if t < n); later rows are not loaded yet
+    for (; t + 2 < n; t += 2) {
+        load_row(ra, lp.node);
+        lp.advance(n, h, len);
+        process_row.template operator()<true>(rb);
+        load_row(rb, lp.node);
+        lp.advance(n, h, len);
+        process_row.template operator()<true>(ra);
+    }
+    if (t + 1 < n) {
+        load_row(ra, lp.node);
+        process_row.template operator()<true>(rb);
+        process_row.template operator()<true>(ra);
+    } else if (t < n) {
+        process_row.template operator()<true>(rb);
+    }
+    emit(parked_node, parked_w, parked);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -317,10 +352,17 @@ __global__ __launch_bounds__(kOpBlock) void k_step_one_peer(
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
     size_t ld, size_t col0, long ncols, int h, int len, float p, float gamma, float mom)
 {
-    if (ZOUT && *unit_w == 0)
-        one_peer_body<V, NEST, ZOUT, true>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom);
-    else
-        one_peer_body<V, NEST, ZOUT, false>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom);
+    const bool full = ((long)blockIdx.x + 1) * (kOpBlock * kOpCols) <= ncols;
+#define SGP_OP_CALL(DIV, MASKED) \
+    one_peer_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom)
+    if (ZOUT && *unit_w == 0) {
+        if (full) SGP_OP_CALL(true, false);
+        else SGP_OP_CALL(true, true);
+    } else {
+        if (full) SGP_OP_CALL(false, false);
+        else SGP_OP_CALL(false, true);
+    }
+#undef SGP_OP_CALL
 }
 
 // ------------------------------------------------------------------------------------------
@@ -715,16 +757,24 @@ __global__ __launch_bounds__(kRowSumBlock) void k_stats_rowsum(const float *__re
 __device__ __forceinline__ void stats_final_body(const double *sums, int n, const float *__restrict__ w,
                                                  double *__restrict__ out)
 {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) out[8 + i] = sqrt(sums[i]);
+    __shared__ double dist[SGP_MAX_NODES];
+    __shared__ float wgt[SGP_MAX_NODES];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const double di = sqrt(sums[i]);
+        dist[i] = di;
+        wgt[i] = w[i];
+        out[8 + i] = di;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         double dmax = 0.0, dmin = 0.0, dsum = 0.0, wsum = 0.0;
         int amax = 0, amin = 0;
         for (int i = 0; i < n; ++i) {
-            double di = sqrt(sums[i]);
+            const double di = dist[i];
             if (i == 0 || di > dmax) { dmax = di; amax = i; }
             if (i == 0 || di < dmin) { dmin = di; amin = i; }
             dsum += di;
-            wsum += (double)w[i];
+            wsum += (double)wgt[i];
         }
         out[0] = dmax;
         out[1] = dsum / (double)n;
@@ -745,15 +795,19 @@ __global__ void k_stats_final(const double *__restrict__ sums, int n, const floa
 
 // Step 2 after the fused kernel: adds the B block sums of k_stats_slotsum in block order and moves
 // every slot's sum to the node that the walk emitted into that slot.
-__global__ __launch_bounds__(64) void k_stats_final_slots(const double *__restrict__ sums2, int B, int n,
-                                                          int hop, int len, const float *__restrict__ w,
-                                                          double *__restrict__ out)
+constexpr int kFinalSlotsBlock = 256;
+__global__ __launch_bounds__(kFinalSlotsBlock) void k_stats_final_slots(
+    const double *__restrict__ sums2, int B, int n, int hop, int len, const float *__restrict__ w,
+    double *__restrict__ out)
 {
+    __shared__ double all[kSlotSumBlocks * (kStatsCache + 1)];
     __shared__ double sums[kStatsCache + 1];
+    for (int i = threadIdx.x; i < B * (kStatsCache + 1); i += kFinalSlotsBlock) all[i] = sums2[i];
+    __syncthreads();
     const int s = threadIdx.x;
     if (s < n || s == kStatsCache) {
         double tot = 0.0;
-        for (int b = 0; b < B; ++b) tot += sums2[(size_t)b * (kStatsCache + 1) + s];
+        for (int b = 0; b < B; ++b) tot += all[b * (kStatsCache + 1) + s];
         sums[s == kStatsCache ? n : stats_slot_node(s, n, hop, len)] = tot;
     }
     __syncthreads();
@@ -1212,7 +1266,7 @@ static int finish_stats(sgp_handle *h, const float *partial, int G, const FusedS
     if (fused) {
         const int B = std::min(kSlotSumBlocks, G);
         hipLaunchKernelGGL(k_stats_slotsum, dim3(B), dim3(kSlotSumBlock), 0, st, partial, G, h->d_sums);
-        hipLaunchKernelGGL(k_stats_final_slots, dim3(1), dim3(64), 0, st, h->d_sums, B, n, fused->hop,
+        hipLaunchKernelGGL(k_stats_final_slots, dim3(1), dim3(kFinalSlotsBlock), 0, st, h->d_sums, B, n, fused->hop,
                            fused->len, w, h->d_result);
     } else {
         hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);

@@ -58,6 +58,21 @@ class RegionMap:
         return sum(1 for c in self.classes if c == cls) * self.granule
 
 
+def smooth_classes(classes: List[int]) -> List[int]:
+    """Regions are contiguous address ranges, so a single granule whose two neighbours agree with
+    each other but not with it is a timing outlier: it takes its neighbours' class.  Classes are then
+    renumbered in order of first appearance."""
+    out = list(classes)
+    for i in range(1, len(out) - 1):
+        if out[i - 1] == out[i + 1] != out[i]:
+            out[i] = out[i - 1]
+    order: List[int] = []
+    for c in out:
+        if c not in order:
+            order.append(c)
+    return [order.index(c) for c in out]
+
+
 def probe_regions(arena: Arena, granule: int = 8 * GIB, probe_d: int = 1 << 22, n: int = 32,
                   max_classes: int = 4) -> RegionMap:
     """Finds which granules of the arena interfere with each other.
@@ -117,7 +132,7 @@ def probe_regions(arena: Arena, granule: int = 8 * GIB, probe_d: int = 1 << 22, 
         if classes[i] < 0:
             classes[i] = max_classes - 1
     eng.close()
-    return RegionMap(granule, classes, first_times, structured)
+    return RegionMap(granule, smooth_classes(classes), first_times, structured)
 
 
 class Placer:

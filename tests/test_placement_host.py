@@ -57,3 +57,12 @@ def test_single_class_map_still_carves_sequentially():
     p = Placer(FakeArena(3 * GIB), m)
     offs = [p.floats(1, 1 << 20, want)[0][0] for want in (0, 1, 2)]
     assert offs == [0, 4 << 20, 8 << 20]
+
+
+def test_smoothing_removes_isolated_outliers_and_renumbers():
+    from paper_1811_10792_amd.placement import smooth_classes
+    raw = [0] * 12 + [1] * 4 + [2] + [1] * 7 + [3] * 11
+    assert smooth_classes(raw) == [0] * 12 + [1] * 12 + [2] * 11
+    assert smooth_classes([0, 0, 1, 1]) == [0, 0, 1, 1]          # a real boundary stays
+    assert smooth_classes([2, 2, 0, 0]) == [0, 0, 1, 1]
+    assert smooth_classes([0]) == [0] and smooth_classes([]) == []
