@@ -3,13 +3,14 @@
 
 A "step" is one pass of the whole hot path over all n simulated nodes: peer schedule, momentum
 update, local step, PushSum mix of x and w, de-bias and (for the workloads that ask for it) the
-consensus statistics, i.e. one sgp_step call plus one sgp_consensus_stats call.  All state and a
+consensus statistics, i.e. one sgp_step_stats call (statistics accumulated inside the step kernel;
+--separate-stats: one sgp_step call plus one sgp_consensus_stats call).  All state and a
 small rotating pool of pre-drawn gradient buffers are resident in HBM before the timed region;
 drawing gradients is not part of the step (g is an input of the method).
 
 Prints ONE JSON line: node-parameter updates per second (n*d*K / wall time of the K steps),
-the roofline of the dominant kernel (the fused step kernel, timed with HIP events on the stream
-it runs on), and the CPU oracle timed on a bounded slice of the same workload.
+the roofline of the dominant kernel (the step kernel, timed with HIP events on the stream it
+runs on), and the CPU oracle timed on a bounded slice of the same workload.
 """
 import argparse
 import json
@@ -163,6 +164,9 @@ def main():
     assert len(kern_ms) == args.steps, (len(kern_ms), args.steps)
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
     bpu = algorithmic_bytes_per_update(wl)
+    fused = do_stats and not args.separate_stats and wl.peers == 1 and not wl.delay and n <= 32 and d % 4 == 0
+    kernel_name = ("k_step_one_peer_stats (step + consensus statistics in one kernel)" if fused else
+                   "k_step_delay" if wl.delay else "k_step_gather" if wl.peers > 1 else "k_step_one_peer")
     achieved = bpu * n * d / avg_kern_s / 1e9
     out = {
         "metric": "SGP node-param updates/sec (n*d/step time)",
@@ -176,7 +180,7 @@ def main():
                    "momentum": wl.momentum, "gamma": wl.gamma,
                    "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool),
                    "placement": alloc.describe()},
-        "roofline": {"bound": "hbm", "kernel": "fused sgp_step kernel",
+        "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
                      "algorithmic_bytes_per_update": bpu,
