@@ -34,6 +34,12 @@
 #ifndef SGP_OP_COLS
 #define SGP_OP_COLS 1
 #endif
+#ifndef SGP_DELAY_BLOCK
+#define SGP_DELAY_BLOCK 256
+#endif
+#ifndef SGP_DELAY_COLS
+#define SGP_DELAY_COLS 2
+#endif
 #ifndef SGP_NT_LOAD
 #define SGP_NT_LOAD 1
 #endif
@@ -440,7 +446,8 @@ __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
 // NM = messages per node known at compile time (0, 1, 2), or -1: read S at run time and fetch the
 // messages while summing.
 // ------------------------------------------------------------------------------------------
-constexpr int kDelayCols = 2;   // 128-bit column groups per work-item
+constexpr int kDelayBlock = SGP_DELAY_BLOCK;   // work-items per block
+constexpr int kDelayCols = SGP_DELAY_COLS;     // 128-bit column groups per work-item
 
 template <int V, bool NEST, int C, int M>
 struct DelayRegs {
@@ -449,7 +456,7 @@ struct DelayRegs {
     int node;
 };
 
-template <int V, bool NEST, bool ZOUT, int NM, bool DIV>
+template <int V, bool NEST, bool ZOUT, int NM, bool DIV, bool MASKED>
 __device__ __forceinline__ void delay_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const float *__restrict__ msg_prev,
@@ -459,16 +466,16 @@ __device__ __forceinline__ void delay_body(
     typedef typename vec_of<V>::type T;
     constexpr int C = kDelayCols;
     constexpr int M = NM > 0 ? NM : 0;
-    const long cbase = (long)blockIdx.x * (kBlock * C) + threadIdx.x;
+    const long cbase = (long)blockIdx.x * (kDelayBlock * C) + threadIdx.x;
     size_t off[C];
     bool live[C];
 #pragma unroll
     for (int j = 0; j < C; ++j) {
-        long c = cbase + (long)j * kBlock;
-        live[j] = c < ncols;
+        long c = cbase + (long)j * kDelayBlock;
+        live[j] = !MASKED || c < ncols;
         off[j] = col0 + (size_t)(live[j] ? c : 0) * V;
     }
-    if (!live[0]) return;
+    if (MASKED && !live[0]) return;
 
     auto load_row = [&](DelayRegs<V, NEST, C, M> &r, int node) {
         r.node = node;
@@ -525,28 +532,44 @@ __device__ __forceinline__ void delay_body(
     };
 
     DelayRegs<V, NEST, C, M> ra, rb;
+    // every row issues the same memory operations, the prefetch inside the loop is unconditional
+    // and full blocks carry no predicates: the compiler can then wait for exactly the loads it needs
     load_row(ra, 0);
-    for (int t = 0; t < n; t += 2) {
-        if (t + 1 < n) load_row(rb, t + 1);
+    int t = 0;                      // ra holds row t; later rows are not loaded yet
+    for (; t + 2 < n; t += 2) {
+        load_row(rb, t + 1);
         process_row(ra);
-        if (t + 2 < n) load_row(ra, t + 2);
-        if (t + 1 < n) process_row(rb);
+        load_row(ra, t + 2);
+        process_row(rb);
+    }
+    if (t + 1 < n) {
+        load_row(rb, t + 1);
+        process_row(ra);
+        process_row(rb);
+    } else {
+        process_row(ra);
     }
 }
 
 template <int V, bool NEST, bool ZOUT, int NM>
-__global__ __launch_bounds__(kBlock) void k_step_delay(
+__global__ __launch_bounds__(kDelayBlock) void k_step_delay(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w,
     const float *__restrict__ msg_prev, float *__restrict__ msg_cur, int n, size_t ld, size_t col0,
     long ncols, const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
 {
-    if (ZOUT && *unit_w == 0)
-        delay_body<V, NEST, ZOUT, NM, true>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols,
-                                            tab_prev, S, p, gamma, mom);
-    else
-        delay_body<V, NEST, ZOUT, NM, false>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols,
-                                             tab_prev, S, p, gamma, mom);
+    const bool full = ((long)blockIdx.x + 1) * (kDelayBlock * kDelayCols) <= ncols;
+#define SGP_DELAY_CALL(DIV, MASKED)                                                                   \
+    delay_body<V, NEST, ZOUT, NM, DIV, MASKED>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols, \
+                                               tab_prev, S, p, gamma, mom)
+    if (ZOUT && *unit_w == 0) {
+        if (full) SGP_DELAY_CALL(true, false);
+        else SGP_DELAY_CALL(true, true);
+    } else {
+        if (full) SGP_DELAY_CALL(false, false);
+        else SGP_DELAY_CALL(false, true);
+    }
+#undef SGP_DELAY_CALL
 }
 
 // Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
@@ -988,7 +1011,7 @@ template <int V, bool NEST, bool ZOUT>
 void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
                   const int *tab_prev, int S)
 {
-    dim3 grid(grid_for(ncols, kBlock * kDelayCols)), block(kBlock);
+    dim3 grid(grid_for(ncols, kDelayBlock * kDelayCols)), block(kDelayBlock);
     const int nm = tab_prev ? S - 1 : 0;
     if (nm == 0)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
