@@ -11,6 +11,8 @@
  *   sgpo_step_*            one SGP iteration, Alg. 1 / Alg. 3, as the dense product of
  *                          eq. "UpdateRule" applied per coordinate
  *   sgpo_step_delay1_*     one iteration of 1-overlap SGP, Alg. 2 with tau = 1
+ *   sgpo_step_osgp_*       one iteration of tau-overlap SGP, Alg. 2 with tau >= 1, and the
+ *                          biased ablation that skips the de-bias
  *   sgpo_debias_*          z = x / w
  *   sgpo_consensus_stats   distance of every node's de-biased parameters to the node-wise
  *                          average (the "parameter deviations" paragraph and figure)

@@ -55,6 +55,10 @@ def _load():
                 f = getattr(lib, "sgpo_step_delay1" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, vp, vp, vp, i32]
                 f.restype = i32
+                f = getattr(lib, "sgpo_step_osgp" + sfx)
+                f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, i32, i64, i32,
+                              vp, vp, vp, vp]
+                f.restype = i32
                 f = getattr(lib, "sgpo_debias" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp]
                 f.restype = None
@@ -145,6 +149,39 @@ def step_delay1(P, x, w, u, g, gamma, m, state: Delay1State, nesterov=True):
     if rc != 0:
         raise MemoryError("oracle step failed")
     state.have_prev = True
+    return z
+
+
+class OsgpState:
+    """The one set of messages that tau-overlap SGP has in flight: what the senders held, the
+    matrix they used and the iteration at which the set is received (-1: nothing in flight)."""
+
+    def __init__(self, n, d, dtype, tau: int):
+        if tau < 1:
+            raise ValueError("tau >= 1 (tau = 0 is plain SGP: use step)")
+        self.tau = tau
+        self.xh_sent = np.zeros((n, d), dtype=dtype)
+        self.w_sent = np.zeros((n,), dtype=dtype)
+        self.P_sent = np.zeros((n, n), dtype=dtype)
+        self.arrival = np.full((1,), -1, dtype=np.int64)
+
+
+def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, biased=False):
+    """Iteration k of tau-overlap SGP (Alg. 2): sends at k % tau == 0 with matrix P, receives what
+    was sent tau iterations ago; biased=True returns z = x (the ablation without push-sum weight)."""
+    dt = x.dtype
+    n, d = x.shape
+    z = np.empty_like(x)
+    up = None if u is None else _chk(u, dt, (n, d))
+    if up is None and nesterov:
+        raise ValueError("momentum needs the buffer u")
+    rc = getattr(_load(), "sgpo_step_osgp" + _sfx(dt))(
+        n, d, _chk(P, dt, (n, n)), _chk(x, dt, (n, d)), _chk(w, dt, (n,)), up,
+        _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)),
+        int(state.tau), int(k), int(bool(biased)), _chk(state.xh_sent, dt, (n, d)),
+        _chk(state.w_sent, dt, (n,)), _chk(state.P_sent, dt, (n, n)), state.arrival.ctypes.data)
+    if rc != 0:
+        raise RuntimeError("oracle step_osgp failed (%d)" % rc)
     return z
 
 

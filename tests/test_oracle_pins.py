@@ -383,6 +383,112 @@ def test_first_delayed_step_receives_nothing():
     assert np.abs(w - 0.5 * w0).max() < 1e-16
 
 
+# ------------------------------------------------ tau-overlap SGP (Alg. 2, tau >= 1), biased form
+def _augmented_tau(Pk, n, tau, sending):
+    """Augmented n(tau+1) x n(tau+1) matrix of the appendix on message delays, block form: first
+    block column = (P_0; P_1; ..; P_tau), identity blocks above the diagonal (virtual nodes forward
+    what they hold).  Deterministic reading: self-messages have delay 0, all others delay tau, and
+    at an iteration without communication every node keeps everything (P_0 = I)."""
+    N = n * (tau + 1)
+    A = np.zeros((N, N))
+    for r in range(tau):
+        A[r * n:(r + 1) * n, (r + 1) * n:(r + 2) * n] = np.eye(n)
+    if sending:
+        D = np.diag(np.diag(Pk))
+        A[:n, :n] = D
+        A[tau * n:, :n] = Pk - D
+    else:
+        A[:n, :n] = np.eye(n)
+    return A
+
+
+@pytest.mark.parametrize("tau", [1, 2, 3])
+@pytest.mark.parametrize("peers", [1, 2])
+@pytest.mark.parametrize("n", [2, 3, 5, 8])
+def test_osgp_matches_virtual_node_model(tau, peers, n):
+    rng = np.random.default_rng(100 * tau + 10 * peers + n)
+    d, gamma, m = 4, 0.05, 0.9
+    x, w, u, _ = _state(rng, n, d)
+    u[:] = 0.0
+    st = O.OsgpState(n, d, F64, tau)
+    X = np.vstack([x.copy()] + [np.zeros((n, d))] * tau)  # virtual nodes start at x = 0, w = 0
+    W = np.concatenate([w.copy(), np.zeros(n * tau)])
+    U = u.copy()
+    total_x0, total_w0 = X.sum(0).copy(), W.sum()
+    drift = np.zeros(d)
+    for k in range(4 * tau + 3):
+        g = rng.standard_normal((n, d))
+        sending = k % tau == 0
+        P = O.mixing_matrix(n, peers, k // tau)
+        A = _augmented_tau(P, n, tau, sending)
+        assert np.abs(A.sum(0) - 1).max() < 1e-15         # column stochastic at every iteration
+        U = m * U + g
+        upd = m * U + g
+        XH = X.copy()
+        XH[:n] -= gamma * upd
+        X, W = A @ XH, A @ W
+        drift += gamma * upd.sum(0)
+        z = O.step_osgp(P, x, w, u, g, gamma, m, st, k, nesterov=True)
+        assert np.abs(x - X[:n]).max() < 1e-13
+        assert np.abs(w - W[:n]).max() < 1e-15
+        assert np.abs(z - X[:n] / W[:n, None]).max() < 1e-12
+        assert np.abs(X.sum(0) - (total_x0 - drift)).max() < 1e-12
+        assert abs(W.sum() - total_w0) < 1e-14
+
+
+def test_osgp_with_tau_one_is_the_one_overlap_oracle():
+    rng = np.random.default_rng(31)
+    n, d = 8, 33
+    for dtype in (F64, F32):
+        x, w, u, _ = _state(rng, n, d, dtype)
+        xa, wa, ua = x.copy(), w.copy(), u.copy()
+        sa, sb = O.Delay1State(n, d, dtype), O.OsgpState(n, d, dtype, 1)
+        for k in range(7):
+            g = rng.standard_normal((n, d)).astype(dtype)
+            P = O.mixing_matrix(n, 2, k, dtype)
+            za = O.step_delay1(P, xa, wa, ua, g, 0.1, 0.9, sa)
+            zb = O.step_osgp(P, x, w, u, g, 0.1, 0.9, sb, k)
+            assert np.array_equal(za, zb) and np.array_equal(xa, x) and np.array_equal(wa, w)
+            assert np.array_equal(ua, u)
+
+
+def test_osgp_weight_closed_form_per_round():
+    # tau = 3, one peer: the common weight changes only at sending iterations and, counted in
+    # rounds c = ceil(k / tau), follows the tau = 1 recursion: 2/3 + (1/3) (-1/2)^c
+    n, d, tau = 8, 2, 3
+    x, w = np.ones((n, d)), np.ones(n)
+    st = O.OsgpState(n, d, F64, tau)
+    for k in range(16):
+        c = -(-k // tau)
+        assert np.abs(w - float(Fraction(2, 3) + Fraction(1, 3) * Fraction(-1, 2) ** c)).max() < 1e-15
+        z = O.step_osgp(O.mixing_matrix(n, 1, k // tau), x, w, None, np.zeros((n, d)), 0.0, 0.0, st, k,
+                        nesterov=False)
+        assert np.abs(z - 1.0).max() < 1e-14               # de-biased consensus is kept ...
+    # ... while the biased form (z = x) reports the drifted numerators
+    x, w = np.ones((n, d)), np.ones(n)
+    st = O.OsgpState(n, d, F64, tau)
+    for k in range(7):
+        z = O.step_osgp(O.mixing_matrix(n, 1, k // tau), x, w, None, np.zeros((n, d)), 0.0, 0.0, st, k,
+                        nesterov=False, biased=True)
+        assert np.array_equal(z, x)
+    assert np.abs(z - w[:, None]).max() < 1e-15 and abs(w[0] - 1.0) > 0.2
+
+
+def test_osgp_between_sends_is_a_local_step():
+    rng = np.random.default_rng(32)
+    n, d, tau = 4, 3, 4
+    x, w, u, g = _state(rng, n, d)
+    st = O.OsgpState(n, d, F64, tau)
+    O.step_osgp(O.mixing_matrix(n, 1, 0), x, w, None, g, 0.5, 0.0, st, 0, nesterov=False)
+    x1, w1 = x.copy(), w.copy()
+    g2 = rng.standard_normal((n, d))
+    z = O.step_osgp(np.full((n, n), np.nan), x, w, None, g2, 0.5, 0.0, st, 1, nesterov=False)
+    assert np.abs(x - (x1 - 0.5 * g2)).max() < 1e-15       # P is not even read
+    assert np.array_equal(w, w1)
+    assert np.abs(z - x / w[:, None]).max() < 1e-15
+    assert st.arrival[0] == tau                            # the first messages are still in flight
+
+
 # ------------------------------------------------------------------ float32 twin, de-bias
 def test_float32_twin_tracks_float64():
     rng = np.random.default_rng(19)
