@@ -51,6 +51,7 @@ extern "C" {
 
 #define SGP_MAX_NODES 1024 /* largest n accepted by sgp_create */
 #define SGP_MAX_PEERS 16   /* largest peers accepted by sgp_create */
+#define SGP_MAX_DELAY 64   /* largest delay (tau) accepted by sgp_create */
 
 typedef struct sgp_handle sgp_handle;
 
@@ -74,9 +75,13 @@ typedef struct sgp_stats {
  *              L = floor(log2(n-1)) + 1 is the length of the peer list 2^0 .. 2^floor(log2(n-1));
  *              a peer reached twice counts once, and each out-neighbour (the node itself
  *              included) gets weight 1/|N_out|.
- *   delay    : 0 = blocking SGP (Alg. 1/3); 1 = 1-overlap SGP (Alg. 2 with tau = 1): the mix at
- *              iteration k uses the node's own share of iteration k and the messages that were
- *              sent at iteration k-1.  The library then owns two [n][ld] message buffers.
+ *   delay    : tau of Alg. 2, 0..SGP_MAX_DELAY.  0 = blocking SGP (Alg. 1/3).  1 = 1-overlap SGP:
+ *              the mix at iteration k uses the node's own share of iteration k and the messages
+ *              that were sent at iteration k-1.  tau >= 2: nodes send only at the iterations with
+ *              k mod tau == 0 (communication round c = k / tau uses the peers of schedule entry c)
+ *              and keep x_i <- xh_i, w_i unchanged at the others; every message is received tau
+ *              iterations after it was sent, i.e. at the next sending iteration.  For delay >= 1
+ *              the library owns two [n][ld] message buffers.
  * Host-only: no device memory is touched until the first call that launches work.
  * Errors: SGP_ERR_INVALID_ARG (out == NULL, n < 1, n > SGP_MAX_NODES, d < 1, ld < d, peers or
  * delay out of range), SGP_ERR_UNSUPPORTED (unknown topology); *out is NULL on error.
@@ -96,6 +101,11 @@ int sgp_destroy(sgp_handle *h);
  * SGP_ERR_SEQUENCE (device resources already set up). */
 int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1);
 
+/* Ablation without the push-sum weight ("biased" overlap SGP in the paper's comparison of 1-OSGP
+ * with its biased implementation): with biased != 0 every later step writes z_i = x_i instead of
+ * x_i / w_i.  w is still updated and reported.  Any delay; takes effect at the next sgp_step. */
+int sgp_set_biased(sgp_handle *h, int biased);
+
 /* Overlap mode: drops the messages in flight, so that the next sgp_step receives nothing (as
  * the first iteration of Alg. 2 does) and may start at any k.  No-op for delay == 0. */
 int sgp_reset(sgp_handle *h);
@@ -112,9 +122,10 @@ int sgp_reset(sgp_handle *h);
  *                                     must not overlap x, m or g
  *   gamma, momentum : step size and Nesterov coefficient
  *   k        >= 0   : iteration index; selects P^(k) (the schedule is a pure function of k)
- * Overlap mode: the first call after sgp_create/sgp_reset receives nothing; every later call
- * must pass the previous k plus one (else SGP_ERR_SEQUENCE and nothing is launched).  Messages
- * sent at the last iteration stay in the library's buffers.
+ * Overlap mode (delay >= 1): the first call after sgp_create/sgp_reset receives nothing and may
+ * start at any k; every later call must pass the previous k plus one (else SGP_ERR_SEQUENCE and
+ * nothing is launched).  Messages sent at the last sending iteration stay in the library's
+ * buffers.
  * Errors: SGP_ERR_INVALID_ARG, SGP_ERR_ALIGNMENT, SGP_ERR_SEQUENCE, SGP_ERR_UNSUPPORTED (more
  * than one peer without delay and n > 256), SGP_ERR_NOMEM, SGP_ERR_HIP.
  */
@@ -158,7 +169,8 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
  *                          (i - 2^((k+r) mod L)) mod n, or -1 likewise
  *   weight               : the uniform mixing weight 1/|N_out| of that iteration
  * Any output pointer may be NULL.  In overlap mode the messages RECEIVED at iteration k are
- * those of sgp_peer_schedule(k-1).
+ * those of sgp_peer_schedule(k - delay).  With delay >= 2 an iteration that is not a multiple of
+ * delay has no peers (all entries -1, weight 1), and iteration k = c * delay uses schedule entry c.
  */
 int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_t *in_peers,
                       float *weight);

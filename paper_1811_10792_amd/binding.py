@@ -27,7 +27,7 @@ SGP_TOPO_DIRECTED_EXP = 0
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
-           "sgp_set_message_buffers", "sgp_step_stats")
+           "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased")
 
 
 class SgpError(RuntimeError):
@@ -83,6 +83,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_copy.argtypes = [vp, vp, i64, vp]
     lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
     lib.sgp_step_stats.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, ctypes.POINTER(_CStats), vp, vp]
+    lib.sgp_set_biased.argtypes = [vp, ctypes.c_int]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -222,6 +223,10 @@ class SGP:
         self._msg_keepalive = (buf0, buf1)
         _check(self._lib.sgp_set_message_buffers(self._h, _ptr(buf0), _ptr(buf1)),
                "sgp_set_message_buffers")
+
+    def set_biased(self, biased: bool) -> None:
+        """Ablation without the push-sum weight: later steps write z = x."""
+        _check(self._lib.sgp_set_biased(self._h, int(biased)), "sgp_set_biased")
 
     def set_kernel_timing(self, enable: bool) -> None:
         _check(self._lib.sgp_set_kernel_timing(self._h, int(enable)), "sgp_set_kernel_timing")

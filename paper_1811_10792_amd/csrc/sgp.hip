@@ -575,7 +575,7 @@ __global__ __launch_bounds__(kDelayBlock) void k_step_delay(
 // Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
 // One block; every work-item reads before anyone writes.
 __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p,
-                        int *__restrict__ unit_w)
+                        int *__restrict__ unit_w, int biased)
 {
     int i = threadIdx.x;
     float acc = 0.0f;
@@ -589,14 +589,22 @@ __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, flo
     }
     const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
     if (i < n) w[i] = acc;
-    if (i == 0) *unit_w = all_one;
+    if (i == 0) *unit_w = all_one | biased;   // biased ablation: z = x, never divide
+}
+
+// Iteration without communication: the weights stay, only the flag is refreshed.
+__global__ void k_w_keep(const float *__restrict__ w, int n, int *__restrict__ unit_w, int biased)
+{
+    int i = threadIdx.x;
+    const int all_one = __syncthreads_and(i >= n || w[i] == 1.0f);
+    if (i == 0) *unit_w = all_one | biased;
 }
 
 // Push-sum weights under one iteration of delay: own share now, the previous iteration's
 // messages (pre-weighted p*w_j) in ascending sender index; the share is also the new message.
 __global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *__restrict__ msgw_cur,
                           int n, const int *__restrict__ tab_prev, int S, float p,
-                          int *__restrict__ unit_w)
+                          int *__restrict__ unit_w, int biased)
 {
     int i = threadIdx.x;
     float own = 0.0f, acc = 0.0f;
@@ -616,7 +624,7 @@ __global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *
         w[i] = acc;
         msgw_cur[i] = own;
     }
-    if (i == 0) *unit_w = all_one;
+    if (i == 0) *unit_w = all_one | biased;   // biased ablation: z = x, never divide
 }
 
 // z = x / w (Alg. 1 line 8) as a stand-alone pass; blockIdx.y = node.
@@ -858,6 +866,7 @@ struct sgp_handle {
     int S;          // sources per receiver = distinct + 1
 
     bool dev_ready;
+    bool biased;        // z = x instead of x / w (ablation without the push-sum weight)
     int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
     int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
@@ -1071,7 +1080,7 @@ int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topol
     if (!out) return SGP_ERR_INVALID_ARG;
     *out = nullptr;
     if (n < 1 || n > SGP_MAX_NODES || d < 1 || ld < d || peers < 1 || peers > SGP_MAX_PEERS ||
-        delay < 0 || delay > 1)
+        delay < 0 || delay > SGP_MAX_DELAY)
         return SGP_ERR_INVALID_ARG;
     if (topology != SGP_TOPO_DIRECTED_EXP) return SGP_ERR_UNSUPPORTED;
     sgp_handle *h = new (std::nothrow) sgp_handle();
@@ -1113,6 +1122,13 @@ int sgp_reset(sgp_handle *h)
     return SGP_OK;
 }
 
+int sgp_set_biased(sgp_handle *h, int biased)
+{
+    if (!h) return SGP_ERR_INVALID_ARG;
+    h->biased = biased != 0;
+    return SGP_OK;
+}
+
 int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1)
 {
     if (!h || !buf0 || !buf1 || buf0 == buf1 || !h->delay || !aligned16(buf0) || !aligned16(buf1))
@@ -1147,7 +1163,19 @@ int sgp_schedule(int32_t n, int32_t peers, int64_t k, int32_t *out_peers, int32_
 int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_t *in_peers,
                       float *weight)
 {
-    if (!h) return SGP_ERR_INVALID_ARG;
+    if (!h || k < 0) return SGP_ERR_INVALID_ARG;
+    if (h->delay > 1) {
+        if (k % h->delay != 0) {   // no communication at this iteration: every node keeps everything
+            const size_t cnt = (size_t)h->n * h->peers;
+            for (size_t q = 0; q < cnt; ++q) {
+                if (out_peers) out_peers[q] = -1;
+                if (in_peers) in_peers[q] = -1;
+            }
+            if (weight) *weight = 1.0f;
+            return SGP_OK;
+        }
+        k /= h->delay;
+    }
     return sgp_schedule(h->n, h->peers, k, out_peers, in_peers, weight);
 }
 
@@ -1170,11 +1198,16 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         (z_out && !aligned4(z_out)))
         return SGP_ERR_ALIGNMENT;
     if (z_out && (z_out == x || z_out == g || (nest && z_out == m))) return SGP_ERR_INVALID_ARG;
-    if (h->delay && h->have_msgs && k != h->last_k + 1) return SGP_ERR_SEQUENCE;
+    if (h->delay && h->last_k >= 0 && k != h->last_k + 1) return SGP_ERR_SEQUENCE;
 
+    // tau >= 2: nodes communicate at the iterations with k mod tau == 0 only, and the schedule
+    // advances once per communication round
+    const int tau = h->delay;
+    const bool sending = tau <= 1 || (k % tau) == 0;
+    const int64_t round = tau > 1 ? k / tau : k;
     const int n = h->n, S = h->S;
-    const Schedule s = make_schedule(n, h->peers, k);
-    const int kmod = h->L > 0 ? (int)(k % h->L) : 0;
+    const Schedule s = make_schedule(n, h->peers, round);
+    const int kmod = h->L > 0 ? (int)(round % h->L) : 0;
     const bool gather = (h->delay == 0 && s.distinct > 1);
     if (gather && n > 256) return SGP_ERR_UNSUPPORTED;
 
@@ -1205,9 +1238,22 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         tev = h->ev[h->ev_head % SGP_TIMING_RING];
     }
 
-    if (h->delay == 0) {
+    if (!sending) {
+        // between two communication rounds: a local step, x <- xh, w unchanged (Alg. 2, else branch
+        // of the send test), which is the one-peer walk with n cycles of length 1 and weight 1
+        hipLaunchKernelGGL(k_w_keep, dim3(1), dim3(wblock), 0, st, w, n, h->d_unit_w, (int)h->biased);
+        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        StepArgs al = a;
+        al.p = 1.0f;
+        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+            if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(al, 0, cols4, 0, 1);
+            if (tail > 0) launch_one_peer<1, NEST, ZOUT>(al, tail0, tail, 0, 1);
+        });
+        h->last_k = k;
+    } else if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
-        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w);
+        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w,
+                           (int)h->biased);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         if (!gather) {
             const int hop = s.distinct ? s.uniq[0] % n : 0;
@@ -1249,12 +1295,12 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     } else {
         const int *tab_prev = nullptr;
         if (h->have_msgs && h->L > 0) {
-            const int kprev = (int)((k - 1) % h->L);
+            const int kprev = (int)((round - 1) % h->L);
             tab_prev = h->d_tab + (size_t)kprev * n * S;
         }
         const int cur = h->cur, prv = cur ^ 1;
         hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
-                           n, tab_prev, S, s.p, h->d_unit_w);
+                           n, tab_prev, S, s.p, h->d_unit_w, (int)h->biased);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0)

@@ -45,9 +45,10 @@ def test_create_validates_arguments(lib):
     assert ok(4, 16, 16, 0, 1, 0) == 0 and h.value
     assert lib.sgp_destroy(h) == 0
     for bad in ((0, 16, 16, 0, 1, 0), (4, 0, 16, 0, 1, 0), (4, 16, 8, 0, 1, 0), (4, 16, 16, 0, 0, 0),
-                (4, 16, 16, 0, 17, 0), (4, 16, 16, 0, 1, 2), (1025, 16, 16, 0, 1, 0)):
+                (4, 16, 16, 0, 17, 0), (4, 16, 16, 0, 1, 65), (4, 16, 16, 0, 1, -1), (1025, 16, 16, 0, 1, 0)):
         assert ok(*bad) == binding.SGP_ERR_INVALID_ARG and not h.value
     assert ok(4, 16, 16, 7, 1, 0) == binding.SGP_ERR_UNSUPPORTED
+    assert ok(4, 16, 16, 0, 1, 64) == 0 and lib.sgp_destroy(h) == 0
     assert lib.sgp_create(None, 4, 16, 16, 0, 1, 0) == binding.SGP_ERR_INVALID_ARG
     assert lib.sgp_destroy(None) == 0
 
@@ -99,3 +100,24 @@ def test_handle_schedule_equals_handle_free(lib):
     for k in range(9):
         assert s.peer_schedule(k) == sgp.sgp_schedule(12, 2, k)
     s.close()
+
+
+def test_schedule_of_tau_overlap_advances_once_per_round(lib):
+    """delay >= 2: peers only at k % delay == 0, and round c = k / delay uses schedule entry c."""
+    n, peers, tau = 8, 2, 3
+    h = ctypes.c_void_p()
+    assert lib.sgp_create(ctypes.byref(h), n, 16, 16, 0, peers, tau) == 0
+    out = (ctypes.c_int32 * (n * peers))()
+    inp = (ctypes.c_int32 * (n * peers))()
+    wt = ctypes.c_float()
+    for k in range(4 * tau):
+        assert lib.sgp_peer_schedule(h, k, ctypes.addressof(out), ctypes.addressof(inp), ctypes.byref(wt)) == 0
+        if k % tau:
+            assert set(out) == {-1} and set(inp) == {-1} and wt.value == 1.0
+        else:
+            ref_out, ref_in, ref_w = binding.sgp_schedule(n, peers, k // tau)
+            assert list(out) == [v for row in ref_out for v in row]
+            assert list(inp) == [v for row in ref_in for v in row]
+            assert wt.value == ref_w
+    assert lib.sgp_set_biased(h, 1) == 0 and lib.sgp_set_biased(None, 1) == binding.SGP_ERR_INVALID_ARG
+    assert lib.sgp_destroy(h) == 0
