@@ -26,16 +26,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes_per_update(wl) -> int:
+def algorithmic_bytes_per_update(wl) -> float:
     """HBM bytes the method itself must move per node-parameter: state read once, state written
     once (the gather costs nothing when a work-item owns a coordinate for all nodes)."""
     nest = wl.momentum != 0.0
     reads = 4 * (2 + (1 if nest else 0))          # x, g, (u)
     writes = 4 * (2 + (1 if nest else 0))         # x, z, (u)
-    if wl.delay:
-        reads += 4                                # previous messages
-        writes += 4                               # new messages
-    return reads + writes
+    total = float(reads + writes)
+    if wl.delay:                                  # previous messages read, new messages written,
+        total += 8.0 / wl.delay                   # at one iteration in every tau
+    return total
 
 
 def read_traffic(workload_name):
@@ -65,13 +65,14 @@ def cpu_baseline(wl, budget_s=15.0):
     u = np.zeros((n, dslice), np.float32)
     w = np.ones(n, np.float32)
     g = syn.normal((n, dslice), wl.grad_std, wl.seed, 4, 0)
-    st = O.Delay1State(n, dslice, np.float32) if wl.delay else None
+    st = O.OsgpState(n, dslice, np.float32, wl.delay) if wl.delay else None
     nest = wl.momentum != 0.0
     steps, t0 = 0, time.perf_counter()
     while True:
-        P = O.mixing_matrix(n, wl.peers, steps, np.float32)
+        P = O.mixing_matrix(n, wl.peers, steps // max(1, wl.delay), np.float32)
         if wl.delay:
-            z = O.step_delay1(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, st, nesterov=nest)
+            z = O.step_osgp(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, st, steps,
+                            nesterov=nest)
         else:
             z = O.step(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, nesterov=nest)
         if wl.stats_each_step:

@@ -22,7 +22,7 @@ class Workload:
     n: int                 # simulated nodes
     d: int                 # parameters per node
     peers: int             # out-peers per iteration on the directed exponential graph
-    delay: int             # 0 = blocking SGP, 1 = messages arrive one iteration late
+    delay: int             # tau: 0 = blocking SGP, 1 = messages arrive one iteration late, ...
     gamma: float
     momentum: float        # 0 -> plain SGD step (Alg. 1), else Nesterov (Alg. 3)
     iterations: int
@@ -33,7 +33,7 @@ class Workload:
     seed: int = 0
 
 
-# The five configurations of the build's baseline description, in its order.
+# The five configurations of the build's baseline description, in its order, then extensions.
 WORKLOADS = {
     "c1_n4_d1k": Workload("c1_n4_d1k", 4, 1024, 1, 0, 0.1, 0.0, 200, "quadratic", 0.01, 1.0),
     "c2_n8_d1m": Workload("c2_n8_d1m", 8, 1 << 20, 1, 0, 0.05, 0.9, 100, "quadratic", 0.1, 1.0),
@@ -44,6 +44,10 @@ WORKLOADS = {
     "c5_n16_transformer_2peer_overlap": Workload("c5_n16_transformer_2peer_overlap", 16,
                                                  213_000_000, 2, 1, 1e-3, 0.9, 20, "fresh",
                                                  1e-4, 0.05),
+    # beyond the baseline description: configuration 5 with tau = 2 (communication every second
+    # iteration, messages two iterations late)
+    "x1_n16_transformer_2peer_tau2": Workload("x1_n16_transformer_2peer_tau2", 16, 213_000_000, 2, 2,
+                                              1e-3, 0.9, 20, "fresh", 1e-4, 0.05),
 }
 
 
