@@ -48,6 +48,9 @@ extern "C" {
 #define SGP_ERR_NOMEM (-6)       /* host or device allocation failed */
 
 #define SGP_TOPO_DIRECTED_EXP 0 /* time-varying directed exponential graph (Appendix A) */
+#define SGP_TOPO_COMPLETE 1     /* every entry of P equal to 1/n: SGP then coincides with parallel
+                                   SGD over AllReduce (section 3, "every entry ... equal to 1/n") */
+#define SGP_TOPO_CUSTOM 2       /* caller-supplied sparse rows of P, see sgp_set_mixing */
 
 #define SGP_MAX_NODES 1024 /* largest n accepted by sgp_create */
 #define SGP_MAX_PEERS 16   /* largest peers accepted by sgp_create */
@@ -69,7 +72,8 @@ typedef struct sgp_stats {
 
 /*
  * Creates a handle for n nodes of d parameters with row stride ld (elements).
- *   topology : SGP_TOPO_DIRECTED_EXP.
+ *   topology : SGP_TOPO_DIRECTED_EXP, or (delay == 0 only) SGP_TOPO_COMPLETE / SGP_TOPO_CUSTOM,
+ *              for which peers is ignored (pass 1).
  *   peers    : out-peers per iteration, 1..SGP_MAX_PEERS (the paper uses 1 and 2).  At iteration
  *              k a node sends to the peers 2^((k+r) mod L) hops ahead, r = 0..peers-1, where
  *              L = floor(log2(n-1)) + 1 is the length of the peer list 2^0 .. 2^floor(log2(n-1));
@@ -84,7 +88,8 @@ typedef struct sgp_stats {
  *              the library owns two [n][ld] message buffers.
  * Host-only: no device memory is touched until the first call that launches work.
  * Errors: SGP_ERR_INVALID_ARG (out == NULL, n < 1, n > SGP_MAX_NODES, d < 1, ld < d, peers or
- * delay out of range), SGP_ERR_UNSUPPORTED (unknown topology); *out is NULL on error.
+ * delay out of range), SGP_ERR_UNSUPPORTED (unknown topology, or a topology other than the
+ * exponential graph with delay > 0); *out is NULL on error.
  */
 int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topology,
                int32_t peers, int32_t delay);
@@ -100,6 +105,30 @@ int sgp_destroy(sgp_handle *h);
  * Errors: SGP_ERR_INVALID_ARG (null, equal or misaligned pointers, delay == 0),
  * SGP_ERR_SEQUENCE (device resources already set up). */
 int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1);
+
+/*
+ * Changes the communication topology (and, for the exponential graph, the number of out-peers) from
+ * the next sgp_step on, for schedules that communicate more at the start of training (the hybrid
+ * AR/1P and 2P/1P schemes of the experiments: complete graph or two peers first, one peer later).
+ * The iteration index k keeps counting.  Blocking mode only: SGP_ERR_UNSUPPORTED if delay > 0.
+ * Synchronises the device when the handle has already launched work.
+ */
+int sgp_set_topology(sgp_handle *h, int32_t topology, int32_t peers);
+
+/*
+ * SGP_TOPO_CUSTOM: sets the mixing matrix used by the following steps as sparse rows, so that any
+ * column-stochastic P with positive diagonal (section 3; non-uniform weights, irregular graphs)
+ * can be run, e.g. the 4-node example of the appendix on message delays.
+ *   in_idx    [n][entries] host : in_idx[i*entries + q] = a node that receiver i hears from (its own
+ *                                 index included if it keeps a share), or -1 for an unused entry
+ *   in_weight [n][entries] host : p_{i,j} of that entry
+ * Receiver i computes sum_q fl(in_weight * xh_j) over its used entries in the order given (list
+ * senders in ascending index to reproduce a dense row-times-vector product).  The arrays are copied;
+ * may be called again between steps (time-varying P).  n <= 256 (n <= 64 on the 128-bit path).
+ * Errors: SGP_ERR_INVALID_ARG (null, entries < 1 or > n, index out of range), SGP_ERR_NOMEM,
+ * SGP_ERR_HIP.  sgp_step on a custom handle without mixing rows returns SGP_ERR_SEQUENCE.
+ */
+int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight, int32_t entries);
 
 /* Ablation without the push-sum weight ("biased" overlap SGP in the paper's comparison of 1-OSGP
  * with its biased implementation): with biased != 0 every later step writes z_i = x_i instead of
@@ -161,7 +190,8 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
                    double *per_node_dist_host, void *stream);
 
 /*
- * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).
+ * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).  Exponential graph only
+ * (SGP_ERR_UNSUPPORTED otherwise).
  *   out_peers [n][peers] : out_peers[i*peers + r] = node that i sends to over its r-th hop,
  *                          (i + 2^((k+r) mod L)) mod n, or -1 if that peer repeats an earlier one
  *                          (or n == 1)

@@ -22,12 +22,15 @@ SGP_ERR_SEQUENCE = -4
 SGP_ERR_HIP = -5
 SGP_ERR_NOMEM = -6
 SGP_TOPO_DIRECTED_EXP = 0
+SGP_TOPO_COMPLETE = 1
+SGP_TOPO_CUSTOM = 2
 
 # every symbol include/sgp.h declares
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
-           "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased")
+           "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
+           "sgp_set_mixing")
 
 
 class SgpError(RuntimeError):
@@ -84,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
     lib.sgp_step_stats.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_set_biased.argtypes = [vp, ctypes.c_int]
+    lib.sgp_set_topology.argtypes = [vp, i32, i32]
+    lib.sgp_set_mixing.argtypes = [vp, vp, vp, i32]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -223,6 +228,20 @@ class SGP:
         self._msg_keepalive = (buf0, buf1)
         _check(self._lib.sgp_set_message_buffers(self._h, _ptr(buf0), _ptr(buf1)),
                "sgp_set_message_buffers")
+
+    def set_topology(self, topology: int, peers: int = 1) -> None:
+        """Switches topology / peer count from the next step on (blocking mode only)."""
+        _check(self._lib.sgp_set_topology(self._h, topology, peers), "sgp_set_topology")
+        self.peers = peers
+
+    def set_mixing(self, in_idx, in_weight) -> None:
+        """SGP_TOPO_CUSTOM: sparse rows of P as [n][entries] lists (index -1 = unused entry)."""
+        n = self.n
+        entries = len(in_idx[0])
+        idx = (ctypes.c_int32 * (n * entries))(*[int(v) for row in in_idx for v in row])
+        wts = (ctypes.c_float * (n * entries))(*[float(v) for row in in_weight for v in row])
+        _check(self._lib.sgp_set_mixing(self._h, ctypes.addressof(idx), ctypes.addressof(wts), entries),
+               "sgp_set_mixing")
 
     def set_biased(self, biased: bool) -> None:
         """Ablation without the push-sum weight: later steps write z = x."""

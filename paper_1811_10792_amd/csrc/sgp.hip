@@ -376,11 +376,12 @@ __global__ __launch_bounds__(kOpBlock) void k_step_one_peer(
 // private LDS column (no barrier: a work-item only reads what it wrote), then each receiver sums
 // its sources.  tab[i*S + q], q < S, lists node i's sources (itself included) in ascending index.
 // ------------------------------------------------------------------------------------------
-template <int V, bool NEST, bool ZOUT, bool DIV>
+template <int V, bool NEST, bool ZOUT, bool DIV, bool WEIGHTED>
 __device__ __forceinline__ void gather_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
-    long ncols, const int *__restrict__ tab, int S, float p, float gamma, float mom)
+    long ncols, const int *__restrict__ tab, const float *__restrict__ tabw, int S, float p,
+    float gamma, float mom)
 {
     typedef typename vec_of<V>::type T;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -411,10 +412,23 @@ __device__ __forceinline__ void gather_body(
     }
     for (int i = 0; i < n; ++i) {
         const int *src = tab + (size_t)i * S;
-        T acc = p * stash[src[0] * kGatherBlock];
-        for (int q = 1; q < S; ++q) {
-            T term = p * stash[src[q] * kGatherBlock];
-            acc = acc + term;
+        T acc = T(0);
+        if (!WEIGHTED) {
+            acc = p * stash[src[0] * kGatherBlock];
+            for (int q = 1; q < S; ++q) {
+                T term = p * stash[src[q] * kGatherBlock];
+                acc = acc + term;
+            }
+        } else {   // own weight per entry; entries < 0 are padding; the first term opens the sum
+            const float *wq = tabw + (size_t)i * S;
+            bool any = false;
+            for (int q = 0; q < S; ++q) {
+                const int j = src[q];
+                if (j < 0) continue;
+                T term = wq[q] * stash[j * kGatherBlock];
+                acc = any ? acc + term : term;
+                any = true;
+            }
         }
         size_t a = (size_t)i * ld + off;
         st_stream<V>(x + a, acc);
@@ -422,17 +436,91 @@ __device__ __forceinline__ void gather_body(
     }
 }
 
-template <int V, bool NEST, bool ZOUT>
+template <int V, bool NEST, bool ZOUT, bool WEIGHTED>
 __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
-    size_t ld, size_t col0, long ncols, const int *__restrict__ tab, int S, float p, float gamma,
-    float mom)
+    size_t ld, size_t col0, long ncols, const int *__restrict__ tab, const float *__restrict__ tabw,
+    int S, float p, float gamma, float mom)
 {
     if (ZOUT && *unit_w == 0)
-        gather_body<V, NEST, ZOUT, true>(x, u, g, z, w, n, ld, col0, ncols, tab, S, p, gamma, mom);
+        gather_body<V, NEST, ZOUT, true, WEIGHTED>(x, u, g, z, w, n, ld, col0, ncols, tab, tabw, S, p,
+                                                   gamma, mom);
     else
-        gather_body<V, NEST, ZOUT, false>(x, u, g, z, w, n, ld, col0, ncols, tab, S, p, gamma, mom);
+        gather_body<V, NEST, ZOUT, false, WEIGHTED>(x, u, g, z, w, n, ld, col0, ncols, tab, tabw, S, p,
+                                                    gamma, mom);
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused step on the complete graph, every entry of P equal to 1/n (the setting in which SGP
+// coincides with parallel SGD over AllReduce, section 3).  All receivers get the same sum
+// sum_j fl(xh_j / n), ascending j, so a work-item adds it up once while it streams the rows
+// (pass 1, pipelined like the one-peer walk) and then writes it to every node (pass 2).
+// ------------------------------------------------------------------------------------------
+template <int V, bool NEST, bool ZOUT, bool DIV, bool MASKED>
+__device__ __forceinline__ void complete_body(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
+    long ncols, float p, float gamma, float mom)
+{
+    typedef typename vec_of<V>::type T;
+    const long c = (long)blockIdx.x * kOpBlock + threadIdx.x;
+    if (MASKED && c >= ncols) return;
+    const size_t off = col0 + (size_t)c * V;
+    struct Row {
+        T x, u, g;
+    } ra, rb;
+    auto load_row = [&](Row &r, int node) {
+        const size_t a = (size_t)node * ld + off;
+        r.x = ld_stream<V>(x + a);
+        if (NEST) r.u = ld_stream<V>(u + a);
+        r.g = ld_stream<V>(g + a);
+    };
+    T acc = T(0);
+    auto process_row = [&](const Row &r, int node) {
+        T xh = half_step<V, NEST>(r.x, NEST ? r.u : r.x, r.g, gamma, mom, u + (size_t)node * ld + off);
+        T term = p * xh;
+        acc = acc + term;
+    };
+    load_row(ra, 0);
+    int t = 0;                      // ra holds row t; later rows are not loaded yet
+    for (; t + 2 < n; t += 2) {
+        load_row(rb, t + 1);
+        process_row(ra, t);
+        load_row(ra, t + 2);
+        process_row(rb, t + 1);
+    }
+    if (t + 1 < n) {
+        load_row(rb, t + 1);
+        process_row(ra, t);
+        process_row(rb, t + 1);
+    } else {
+        process_row(ra, t);
+    }
+    for (int i = 0; i < n; ++i) {
+        const size_t a = (size_t)i * ld + off;
+        st_stream<V>(x + a, acc);
+        if (ZOUT) st_stream<V>(z + a, debias_val<V, DIV>(acc, DIV ? w[i] : 1.0f));
+    }
+}
+
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kOpBlock) void k_step_complete(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
+    size_t ld, size_t col0, long ncols, float p, float gamma, float mom)
+{
+    const bool full = ((long)blockIdx.x + 1) * kOpBlock <= ncols;
+#define SGP_COMPLETE_CALL(DIV, MASKED) \
+    complete_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, p, gamma, mom)
+    if (ZOUT && *unit_w == 0) {
+        if (full) SGP_COMPLETE_CALL(true, false);
+        else SGP_COMPLETE_CALL(true, true);
+    } else {
+        if (full) SGP_COMPLETE_CALL(false, false);
+        else SGP_COMPLETE_CALL(false, true);
+    }
+#undef SGP_COMPLETE_CALL
 }
 
 // ------------------------------------------------------------------------------------------
@@ -590,6 +678,42 @@ __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, flo
     const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
     if (i < n) w[i] = acc;
     if (i == 0) *unit_w = all_one | biased;   // biased ablation: z = x, never divide
+}
+
+// Complete graph: every node ends with the same weight sum_j fl(p * w_j), ascending j.
+__global__ void k_w_complete(float *w, int n, float p, int *__restrict__ unit_w, int biased)
+{
+    int i = threadIdx.x;
+    float acc = 0.0f;
+    if (i < n)
+        for (int j = 0; j < n; ++j) {
+            float term = p * w[j];
+            acc = acc + term;
+        }
+    const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
+    if (i < n) w[i] = acc;
+    if (i == 0) *unit_w = all_one | biased;
+}
+
+// Caller-supplied sparse rows: w_i <- sum over the row's entries, in the order given, of weight * w_j.
+__global__ void k_w_custom(float *w, int n, const int *__restrict__ tab, const float *__restrict__ tabw,
+                           int S, int *__restrict__ unit_w, int biased)
+{
+    int i = threadIdx.x;
+    float acc = 0.0f;
+    if (i < n) {
+        bool any = false;
+        for (int q = 0; q < S; ++q) {
+            const int j = tab[(size_t)i * S + q];
+            if (j < 0) continue;
+            float term = tabw[(size_t)i * S + q] * w[j];
+            acc = any ? acc + term : term;
+            any = true;
+        }
+    }
+    const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
+    if (i < n) w[i] = acc;
+    if (i == 0) *unit_w = all_one | biased;
 }
 
 // Iteration without communication: the weights stay, only the flag is refreshed.
@@ -868,6 +992,10 @@ struct sgp_handle {
     bool dev_ready;
     bool biased;        // z = x instead of x / w (ablation without the push-sum weight)
     int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
+    bool tab_stale;     // topology or peer count changed: rebuild d_tab before the next step
+    int cS;             // caller-supplied mixing rows (SGP_TOPO_CUSTOM): entries per row, 0 = not set
+    int *d_cidx;        // [n][cS] senders, -1 = padding
+    float *d_cw;        // [n][cS] weights
     int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
     float *d_partial_f; // [(n+1)][Gf] partial sums written by the fused step+statistics kernel
@@ -931,9 +1059,13 @@ void build_tables(const sgp_handle *h, int *tab)
     }
 }
 
-int ensure_device(sgp_handle *h)
+// (Re)builds the source tables of the directed exponential graph for the handle's current peers.
+int upload_tables(sgp_handle *h)
 {
-    if (h->dev_ready) return SGP_OK;
+    if (h->d_tab) {
+        (void)hipFree(h->d_tab);   // waits for the kernels that still read it
+        h->d_tab = nullptr;
+    }
     const int n = h->n, S = h->S, tables = h->L > 0 ? h->L : 1;
     size_t tab_elems = (size_t)tables * n * S;
     int *host_tab = static_cast<int *>(std::malloc(tab_elems * sizeof(int)));
@@ -944,6 +1076,17 @@ int ensure_device(sgp_handle *h)
         e = hipMemcpy(h->d_tab, host_tab, tab_elems * sizeof(int), hipMemcpyHostToDevice);
     std::free(host_tab);
     if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+    h->tab_stale = false;
+    return SGP_OK;
+}
+
+int ensure_device(sgp_handle *h)
+{
+    if (h->dev_ready) return h->tab_stale ? upload_tables(h) : SGP_OK;
+    const int n = h->n;
+    int rc = upload_tables(h);
+    if (rc != SGP_OK) return rc;
+    hipError_t e;
 
     h->G = kStatsGridMax;
     e = hipMalloc(&h->d_unit_w, sizeof(int));
@@ -974,6 +1117,8 @@ void release_device(sgp_handle *h)
             (void)hipEventDestroy(h->ev[i][1]);
         }
     if (h->d_tab) (void)hipFree(h->d_tab);
+    if (h->d_cidx) (void)hipFree(h->d_cidx);
+    if (h->d_cw) (void)hipFree(h->d_cw);
     if (h->d_unit_w) (void)hipFree(h->d_unit_w);
     if (h->d_partial) (void)hipFree(h->d_partial);
     if (h->d_partial_f) (void)hipFree(h->d_partial_f);
@@ -1008,12 +1153,24 @@ void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 }
 
 template <int V, bool NEST, bool ZOUT>
-void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, int S)
+void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S)
 {
     size_t lds = (size_t)a.n * kGatherBlock * V * sizeof(float);
-    hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT>), dim3(grid_for(ncols, kGatherBlock)),
-                       dim3(kGatherBlock), lds, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld,
-                       col0, ncols, tab, S, a.p, a.gamma, a.mom);
+    dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
+    if (tabw)
+        hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, true>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.gamma, a.mom);
+    else
+        hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, false>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.gamma, a.mom);
+}
+
+template <int V, bool NEST, bool ZOUT>
+void launch_complete(const StepArgs &a, size_t col0, long ncols)
+{
+    hipLaunchKernelGGL((k_step_complete<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
+                       0, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, a.p,
+                       a.gamma, a.mom);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -1082,7 +1239,9 @@ int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topol
     if (n < 1 || n > SGP_MAX_NODES || d < 1 || ld < d || peers < 1 || peers > SGP_MAX_PEERS ||
         delay < 0 || delay > SGP_MAX_DELAY)
         return SGP_ERR_INVALID_ARG;
-    if (topology != SGP_TOPO_DIRECTED_EXP) return SGP_ERR_UNSUPPORTED;
+    if (topology != SGP_TOPO_DIRECTED_EXP && topology != SGP_TOPO_COMPLETE && topology != SGP_TOPO_CUSTOM)
+        return SGP_ERR_UNSUPPORTED;
+    if (topology != SGP_TOPO_DIRECTED_EXP && delay != 0) return SGP_ERR_UNSUPPORTED;
     sgp_handle *h = new (std::nothrow) sgp_handle();
     if (!h) return SGP_ERR_NOMEM;
     std::memset(h, 0, sizeof(*h));
@@ -1119,6 +1278,46 @@ int sgp_reset(sgp_handle *h)
     if (!h) return SGP_ERR_INVALID_ARG;
     h->have_msgs = false;
     h->last_k = -1;
+    return SGP_OK;
+}
+
+int sgp_set_topology(sgp_handle *h, int32_t topology, int32_t peers)
+{
+    if (!h || peers < 1 || peers > SGP_MAX_PEERS) return SGP_ERR_INVALID_ARG;
+    if (topology != SGP_TOPO_DIRECTED_EXP && topology != SGP_TOPO_COMPLETE && topology != SGP_TOPO_CUSTOM)
+        return SGP_ERR_UNSUPPORTED;
+    if (h->delay != 0) return SGP_ERR_UNSUPPORTED;
+    h->topology = topology;
+    h->peers = peers;
+    Schedule s = make_schedule(h->n, peers, 0);
+    h->L = s.L;
+    h->distinct = s.distinct;
+    h->S = s.distinct + 1;
+    h->tab_stale = true;
+    return SGP_OK;
+}
+
+int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight, int32_t entries)
+{
+    if (!h || !in_idx || !in_weight || entries < 1 || entries > h->n) return SGP_ERR_INVALID_ARG;
+    const size_t cnt = (size_t)h->n * entries;
+    for (size_t q = 0; q < cnt; ++q)
+        if (in_idx[q] < -1 || in_idx[q] >= h->n) return SGP_ERR_INVALID_ARG;
+    if (h->d_cidx) {   // hipFree waits for the kernels that still read the old rows
+        (void)hipFree(h->d_cidx);
+        h->d_cidx = nullptr;
+    }
+    if (h->d_cw) {
+        (void)hipFree(h->d_cw);
+        h->d_cw = nullptr;
+    }
+    h->cS = 0;
+    hipError_t e = hipMalloc(&h->d_cidx, cnt * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc(&h->d_cw, cnt * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(h->d_cidx, in_idx, cnt * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(h->d_cw, in_weight, cnt * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+    h->cS = entries;
     return SGP_OK;
 }
 
@@ -1164,6 +1363,7 @@ int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_
                       float *weight)
 {
     if (!h || k < 0) return SGP_ERR_INVALID_ARG;
+    if (h->topology != SGP_TOPO_DIRECTED_EXP) return SGP_ERR_UNSUPPORTED;
     if (h->delay > 1) {
         if (k % h->delay != 0) {   // no communication at this iteration: every node keeps everything
             const size_t cnt = (size_t)h->n * h->peers;
@@ -1208,7 +1408,10 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     const int n = h->n, S = h->S;
     const Schedule s = make_schedule(n, h->peers, round);
     const int kmod = h->L > 0 ? (int)(round % h->L) : 0;
-    const bool gather = (h->delay == 0 && s.distinct > 1);
+    const bool complete = h->topology == SGP_TOPO_COMPLETE;
+    const bool custom = h->topology == SGP_TOPO_CUSTOM;
+    if (custom && h->cS == 0) return SGP_ERR_SEQUENCE;         // sgp_set_mixing has not been called
+    const bool gather = custom || (h->delay == 0 && !complete && s.distinct > 1);
     if (gather && n > 256) return SGP_ERR_UNSUPPORTED;
 
     int rc = ensure_device(h);
@@ -1250,6 +1453,24 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             if (tail > 0) launch_one_peer<1, NEST, ZOUT>(al, tail0, tail, 0, 1);
         });
         h->last_k = k;
+    } else if (complete) {
+        StepArgs ac = a;
+        ac.p = 1.0f / (float)n;
+        hipLaunchKernelGGL(k_w_complete, dim3(1), dim3(wblock), 0, st, w, n, ac.p, h->d_unit_w,
+                           (int)h->biased);
+        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+            if (cols4 > 0) launch_complete<4, NEST, ZOUT>(ac, 0, cols4);
+            if (tail > 0) launch_complete<1, NEST, ZOUT>(ac, tail0, tail);
+        });
+    } else if (custom) {
+        hipLaunchKernelGGL(k_w_custom, dim3(1), dim3(wblock), 0, st, w, n, h->d_cidx, h->d_cw, h->cS,
+                           h->d_unit_w, (int)h->biased);
+        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+            if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS);
+            if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS);
+        });
     } else if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
         hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w,
@@ -1288,8 +1509,8 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             });
         } else {
             dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-                if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, tab_k, S);
-                if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, tab_k, S);
+                if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, tab_k, nullptr, S);
+                if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, tab_k, nullptr, S);
             });
         }
     } else {
