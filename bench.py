@@ -69,7 +69,10 @@ def cpu_baseline(wl, budget_s=15.0):
     nest = wl.momentum != 0.0
     steps, t0 = 0, time.perf_counter()
     while True:
-        P = O.mixing_matrix(n, wl.peers, steps // max(1, wl.delay), np.float32)
+        if wl.topology == "complete":
+            P = np.full((n, n), np.float32(1.0) / np.float32(n), dtype=np.float32)
+        else:
+            P = O.mixing_matrix(n, wl.peers, steps // max(1, wl.delay), np.float32)
         if wl.delay:
             z = O.step_osgp(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, st, steps,
                             nesterov=nest)
@@ -121,7 +124,8 @@ def main():
     nest = wl.momentum != 0.0
     ld = syn.padded_ld(d)                 # rows start on 1 KiB boundaries
     alloc = StateAllocator(args.placement)
-    eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
+    complete = wl.topology == "complete"
+    eng = sgp.SGP(n, d, ld, topology=1 if complete else 0, peers=wl.peers, delay=wl.delay)
     X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3, out=alloc.floats("x", n, ld))
     U = alloc.floats("u", n, ld).zero_()
     W = torch.ones(n, dtype=torch.float32, device="cuda")
@@ -165,9 +169,13 @@ def main():
     assert len(kern_ms) == args.steps, (len(kern_ms), args.steps)
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
     bpu = algorithmic_bytes_per_update(wl)
-    fused = do_stats and not args.separate_stats and wl.peers == 1 and not wl.delay and n <= 32 and d % 4 == 0
+    fused = (do_stats and not args.separate_stats and wl.peers == 1 and not wl.delay and n <= 32
+             and d % 4 == 0 and not complete)
     kernel_name = ("k_step_one_peer_stats (step + consensus statistics in one kernel)" if fused else
-                   "k_step_delay" if wl.delay else "k_step_gather" if wl.peers > 1 else "k_step_one_peer")
+                   "k_step_complete" if complete else
+                   "k_step_delay" if wl.delay == 1 else
+                   "k_step_delay every %d-th iteration, k_step_one_peer otherwise" % wl.delay if wl.delay else
+                   "k_step_gather" if wl.peers > 1 else "k_step_one_peer")
     achieved = bpu * n * d / avg_kern_s / 1e9
     out = {
         "metric": "SGP node-param updates/sec (n*d/step time)",
@@ -177,7 +185,8 @@ def main():
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "peers": wl.peers, "delay": wl.delay,
+        "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "topology": wl.topology,
+                   "peers": wl.peers, "delay": wl.delay,
                    "momentum": wl.momentum, "gamma": wl.gamma,
                    "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool),
                    "placement": alloc.describe()},

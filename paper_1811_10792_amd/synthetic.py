@@ -31,6 +31,7 @@ class Workload:
     x_std: float           # std of the initial x
     stats_each_step: bool = False
     seed: int = 0
+    topology: str = "exp"  # "exp": directed exponential graph; "complete": every entry of P is 1/n
 
 
 # The five configurations of the build's baseline description, in its order, then extensions.
@@ -48,6 +49,9 @@ WORKLOADS = {
     # iteration, messages two iterations late)
     "x1_n16_transformer_2peer_tau2": Workload("x1_n16_transformer_2peer_tau2", 16, 213_000_000, 2, 2,
                                               1e-3, 0.9, 20, "fresh", 1e-4, 0.05),
+    # configuration 4's shape on the complete graph (the AllReduce-equivalent end of the hybrid schemes)
+    "x2_n32_resnet50_complete": Workload("x2_n32_resnet50_complete", 32, 25_557_032, 1, 0, 0.1, 0.9, 50,
+                                         "fresh", 1e-3, 0.05, topology="complete"),
 }
 
 
