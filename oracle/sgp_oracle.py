@@ -50,14 +50,14 @@ def _load():
                 f.argtypes = [i32, i32, i64, vp]
                 f.restype = None
                 f = getattr(lib, "sgpo_step" + sfx)
-                f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32]
+                f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, real, i32]
                 f.restype = i32
                 f = getattr(lib, "sgpo_step_delay1" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, vp, vp, vp, i32]
                 f.restype = i32
                 f = getattr(lib, "sgpo_step_osgp" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, i32, i64, i32,
-                              vp, vp, vp, vp]
+                              vp, vp, vp, vp, real, i32]
                 f.restype = i32
                 f = getattr(lib, "sgpo_debias" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp]
@@ -102,9 +102,9 @@ def mixing_matrix(n: int, peers: int, k: int, dtype=np.float64) -> np.ndarray:
     return P
 
 
-def step(P, x, w, u, g, gamma, m, nesterov=True):
+def step(P, x, w, u, g, gamma, m, nesterov=True, wd=0.0, wd_on_x=False):
     """One SGP iteration with mixing matrix P (Alg. 1 if nesterov is False, else Alg. 3).
-    Updates x, w (and u) in place and returns z."""
+    Updates x, w (and u) in place and returns z.  wd: weight decay, g + wd * z (or wd * x)."""
     dt = x.dtype
     n, d = x.shape
     z = np.empty_like(x)
@@ -116,7 +116,8 @@ def step(P, x, w, u, g, gamma, m, nesterov=True):
         up = _chk(u, dt, (n, d))
     rc = getattr(_load(), "sgpo_step" + _sfx(dt))(
         n, d, _chk(P, dt, (n, n)), _chk(x, dt, (n, d)), _chk(w, dt, (n,)), up,
-        _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)))
+        _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)),
+        float(wd), int(bool(wd_on_x)))
     if rc != 0:
         raise MemoryError("oracle step failed")
     return z
@@ -166,7 +167,8 @@ class OsgpState:
         self.arrival = np.full((1,), -1, dtype=np.int64)
 
 
-def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, biased=False):
+def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, biased=False,
+              wd=0.0, wd_on_x=False):
     """Iteration k of tau-overlap SGP (Alg. 2): sends at k % tau == 0 with matrix P, receives what
     was sent tau iterations ago; biased=True returns z = x (the ablation without push-sum weight)."""
     dt = x.dtype
@@ -179,7 +181,8 @@ def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, 
         n, d, _chk(P, dt, (n, n)), _chk(x, dt, (n, d)), _chk(w, dt, (n,)), up,
         _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)),
         int(state.tau), int(k), int(bool(biased)), _chk(state.xh_sent, dt, (n, d)),
-        _chk(state.w_sent, dt, (n,)), _chk(state.P_sent, dt, (n, n)), state.arrival.ctypes.data)
+        _chk(state.w_sent, dt, (n,)), _chk(state.P_sent, dt, (n, n)), state.arrival.ctypes.data,
+        float(wd), int(bool(wd_on_x)))
     if rc != 0:
         raise RuntimeError("oracle step_osgp failed (%d)" % rc)
     return z

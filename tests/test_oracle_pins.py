@@ -283,6 +283,55 @@ def test_single_node_is_plain_nesterov_sgd_library():
         assert np.abs(u[0] - opt.state[p]["momentum_buffer"].numpy()).max() < 1e-13
 
 
+@pytest.mark.parametrize("nesterov,m", [(False, 0.0), (True, 0.9)])
+def test_weight_decay_is_the_library_optimizers(nesterov, m):
+    # one node: x = z, and SGP with weight decay is torch.optim.SGD(weight_decay=...)
+    d, gamma, wd = 12, 0.1, 0.05
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((1, d))
+    p = torch.tensor(x[0].copy(), requires_grad=True)
+    opt = torch.optim.SGD([p], lr=gamma, momentum=m, nesterov=nesterov, weight_decay=wd)
+    w, u = np.ones(1), np.zeros((1, d))
+    for k in range(8):
+        g = rng.standard_normal((1, d))
+        z = O.step(np.ones((1, 1)), x, w, u, g, gamma, m, nesterov=nesterov, wd=wd, wd_on_x=bool(k & 1))
+        p.grad = torch.tensor(g[0].copy())
+        opt.step()
+        assert np.abs(z[0] - p.detach().numpy()).max() < 1e-13
+
+
+def test_weight_decay_acts_on_z_or_on_x():
+    # equivalent to handing over g + wd * theta, with theta = x / w (default) or x
+    rng = np.random.default_rng(42)
+    n, d, wd = 5, 7, 0.03
+    P = _random_column_stochastic(rng, n)
+    x, w, u, g = _state(rng, n, d)
+    for on_x in (False, True):
+        theta = x if on_x else x / w[:, None]
+        xa, wa, ua = x.copy(), w.copy(), u.copy()
+        za = O.step(P, xa, wa, ua, g, 0.1, 0.9, wd=wd, wd_on_x=on_x)
+        xb, wb, ub = x.copy(), w.copy(), u.copy()
+        zb = O.step(P, xb, wb, ub, g + wd * theta, 0.1, 0.9)
+        assert np.abs(xa - xb).max() < 1e-15 and np.abs(za - zb).max() < 1e-14
+        assert np.abs(ua - ub).max() < 1e-15 and np.array_equal(wa, wb)
+        # same through the overlap oracle
+        st1, st2 = O.OsgpState(n, d, F64, 2), O.OsgpState(n, d, F64, 2)
+        xa, wa, ua = x.copy(), w.copy(), u.copy()
+        xb, wb, ub = x.copy(), w.copy(), u.copy()
+        for k in range(3):
+            th = xb if on_x else xb / wb[:, None]
+            gb = g + wd * th
+            za = O.step_osgp(P, xa, wa, ua, g, 0.1, 0.9, st1, k, wd=wd, wd_on_x=on_x)
+            zb = O.step_osgp(P, xb, wb, ub, gb, 0.1, 0.9, st2, k)
+            assert np.abs(xa - xb).max() < 1e-14 and np.abs(za - zb).max() < 1e-13
+    # and the two variants differ when w != 1
+    xa, wa, ua = x.copy(), w.copy(), u.copy()
+    xb, wb, ub = x.copy(), w.copy(), u.copy()
+    O.step(P, xa, wa, ua, g, 0.1, 0.9, wd=wd, wd_on_x=False)
+    O.step(P, xb, wb, ub, g, 0.1, 0.9, wd=wd, wd_on_x=True)
+    assert np.abs(xa - xb).max() > 1e-4
+
+
 def test_zero_momentum_reduces_alg3_to_alg1():
     rng = np.random.default_rng(16)
     for dtype in (F64, F32):
