@@ -130,6 +130,19 @@ int sgp_set_topology(sgp_handle *h, int32_t topology, int32_t peers);
  */
 int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight, int32_t entries);
 
+/*
+ * Weight decay fused into the local step (the hyperparameter appendix: the ImageNet runs use
+ * weight decay 1e-4 with Nesterov momentum): from the next sgp_step on, g_i is replaced by
+ * g_i + weight_decay * theta_i before Alg. 1 line 4 / Alg. 3 lines 4-5, where theta_i is the
+ * de-biased z_i^(k) = x_i^(k) / w_i^(k) (on_numerator == 0; the gradient of the L2 term at the
+ * point where g_i was evaluated) or the numerator x_i^(k) (on_numerator != 0; what an optimizer
+ * that steps on the biased parameters applies).  The paper does not say which; they coincide
+ * whenever w = 1, i.e. for blocking SGP on the exponential graph.  With sgp_set_biased the
+ * numerator is used.  weight_decay = 0 switches it off.  Costs no extra memory traffic (x is
+ * read anyway).  Errors: SGP_ERR_INVALID_ARG (null handle, negative or NaN coefficient).
+ */
+int sgp_set_weight_decay(sgp_handle *h, float weight_decay, int on_numerator);
+
 /* Ablation without the push-sum weight ("biased" overlap SGP in the paper's comparison of 1-OSGP
  * with its biased implementation): with biased != 0 every later step writes z_i = x_i instead of
  * x_i / w_i.  w is still updated and reported.  Any delay; takes effect at the next sgp_step. */

@@ -30,7 +30,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
-           "sgp_set_mixing")
+           "sgp_set_mixing", "sgp_set_weight_decay")
 
 
 class SgpError(RuntimeError):
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
     lib.sgp_step_stats.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_set_biased.argtypes = [vp, ctypes.c_int]
+    lib.sgp_set_weight_decay.argtypes = [vp, f32, ctypes.c_int]
     lib.sgp_set_topology.argtypes = [vp, i32, i32]
     lib.sgp_set_mixing.argtypes = [vp, vp, vp, i32]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
@@ -242,6 +243,11 @@ class SGP:
         wts = (ctypes.c_float * (n * entries))(*[float(v) for row in in_weight for v in row])
         _check(self._lib.sgp_set_mixing(self._h, ctypes.addressof(idx), ctypes.addressof(wts), entries),
                "sgp_set_mixing")
+
+    def set_weight_decay(self, weight_decay: float, on_numerator: bool = False) -> None:
+        """g + weight_decay * z (or * x with on_numerator) from the next step on."""
+        _check(self._lib.sgp_set_weight_decay(self._h, weight_decay, int(on_numerator)),
+               "sgp_set_weight_decay")
 
     def set_biased(self, biased: bool) -> None:
         """Ablation without the push-sum weight: later steps write z = x."""

@@ -145,25 +145,43 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
+// Step size, momentum and weight decay of the local optimiser step, as the kernels take them.
+struct Hyper {
+    float gamma;          // step size
+    float mom;            // Nesterov coefficient
+    float wd;             // weight decay coefficient
+    int wd_mode;          // 0: none; 1: decay acts on the numerator x; 2: on the de-biased x / w^(k)
+    const float *w_old;   // [n] weights before this iteration's update (read when wd_mode == 2)
+};
+
 // Local optimiser step on the numerator.  Alg. 3 lines 4-5: u <- m u + g; xh = x - gamma (m u + g)
-// with the NEW u.  Alg. 1 line 4: xh = x - gamma g.
+// with the NEW u.  Alg. 1 line 4: xh = x - gamma g.  With weight decay g is replaced by
+// g + wd * theta, theta = x or x / w_old (the hyperparameter appendix names a weight decay of 1e-4
+// without saying which copy of the parameters it acts on; both are offered).
 template <int V, bool NEST>
 __device__ __forceinline__ typename vec_of<V>::type half_step(typename vec_of<V>::type xv,
                                                              typename vec_of<V>::type uv,
                                                              typename vec_of<V>::type gv,
-                                                             float gamma, float mom, float *u_dst)
+                                                             const Hyper &hp, float *u_dst,
+                                                             float w_old)
 {
     typedef typename vec_of<V>::type T;
+    if (hp.wd_mode != 0) {   // uniform over the grid
+        T th = xv;
+        if (hp.wd_mode == 2) th = xv / w_old;
+        T dec = hp.wd * th;
+        gv = gv + dec;
+    }
     if (NEST) {
-        T mu = mom * uv;
+        T mu = hp.mom * uv;
         T un = mu + gv;
         st_stream<V>(u_dst, un);
-        T mun = mom * un;
+        T mun = hp.mom * un;
         T dir = mun + gv;
-        T stp = gamma * dir;
+        T stp = hp.gamma * dir;
         return xv - stp;
     } else {
-        T stp = gamma * gv;
+        T stp = hp.gamma * gv;
         return xv - stp;
     }
 }
@@ -201,7 +219,8 @@ constexpr int kOpCols = SGP_OP_COLS;     // 128-bit column groups per work-item
 template <int V, bool NEST, int C>
 struct RowRegs {
     typename vec_of<V>::type x[C], u[C], g[C];
-    float w;
+    float w;    // new weight of the node (de-bias)
+    float wo;   // its weight before this iteration (weight decay on the de-biased parameters)
     int node;
 };
 
@@ -233,7 +252,7 @@ template <int V, bool NEST, bool ZOUT, bool DIV, bool MASKED>
 __device__ __forceinline__ void one_peer_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
-    long ncols, int h, int len, float p, float gamma, float mom)
+    long ncols, int h, int len, float p, Hyper hp)
 {
     typedef typename vec_of<V>::type T;
     constexpr int C = kOpCols;
@@ -251,6 +270,7 @@ __device__ __forceinline__ void one_peer_body(
     auto load_row = [&](RowRegs<V, NEST, C> &r, int node) {
         r.node = node;
         r.w = (ZOUT && DIV) ? w[node] : 1.0f;
+        r.wo = hp.wd_mode == 2 ? hp.w_old[node] : 1.0f;
         const size_t row = (size_t)node * ld;
 #pragma unroll
         for (int j = 0; j < C; ++j)
@@ -287,8 +307,8 @@ __device__ __forceinline__ void one_peer_body(
         for (int j = 0; j < C; ++j) {
             T xh = T(0);
             if (live[j])
-                xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom,
-                                        u + row + off[j]);
+                xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], hp,
+                                        u + row + off[j], r.wo);
             if (opens) {
                 xn[j] = parked[j];
                 first[j] = xh;
@@ -356,11 +376,11 @@ template <int V, bool NEST, bool ZOUT>
 __global__ __launch_bounds__(kOpBlock) void k_step_one_peer(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
-    size_t ld, size_t col0, long ncols, int h, int len, float p, float gamma, float mom)
+    size_t ld, size_t col0, long ncols, int h, int len, float p, Hyper hp)
 {
     const bool full = ((long)blockIdx.x + 1) * (kOpBlock * kOpCols) <= ncols;
 #define SGP_OP_CALL(DIV, MASKED) \
-    one_peer_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, gamma, mom)
+    one_peer_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, h, len, p, hp)
     if (ZOUT && *unit_w == 0) {
         if (full) SGP_OP_CALL(true, false);
         else SGP_OP_CALL(true, true);
@@ -381,7 +401,7 @@ __device__ __forceinline__ void gather_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
     long ncols, const int *__restrict__ tab, const float *__restrict__ tabw, int S, float p,
-    float gamma, float mom)
+    Hyper hp)
 {
     typedef typename vec_of<V>::type T;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -406,7 +426,8 @@ __device__ __forceinline__ void gather_body(
             if (i0 + q < n) {
                 size_t a = (size_t)(i0 + q) * ld + off;
                 stash[(i0 + q) * kGatherBlock] =
-                    half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], gamma, mom, u + a);
+                    half_step<V, NEST>(xv[q], NEST ? uv[q] : xv[q], gv[q], hp, u + a,
+                                       hp.wd_mode == 2 ? hp.w_old[i0 + q] : 1.0f);
             }
         }
     }
@@ -441,14 +462,14 @@ __global__ __launch_bounds__(kGatherBlock) void k_step_gather(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
     size_t ld, size_t col0, long ncols, const int *__restrict__ tab, const float *__restrict__ tabw,
-    int S, float p, float gamma, float mom)
+    int S, float p, Hyper hp)
 {
     if (ZOUT && *unit_w == 0)
         gather_body<V, NEST, ZOUT, true, WEIGHTED>(x, u, g, z, w, n, ld, col0, ncols, tab, tabw, S, p,
-                                                   gamma, mom);
+                                                   hp);
     else
         gather_body<V, NEST, ZOUT, false, WEIGHTED>(x, u, g, z, w, n, ld, col0, ncols, tab, tabw, S, p,
-                                                    gamma, mom);
+                                                    hp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -461,7 +482,7 @@ template <int V, bool NEST, bool ZOUT, bool DIV, bool MASKED>
 __device__ __forceinline__ void complete_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, int n, size_t ld, size_t col0,
-    long ncols, float p, float gamma, float mom)
+    long ncols, float p, Hyper hp)
 {
     typedef typename vec_of<V>::type T;
     const long c = (long)blockIdx.x * kOpBlock + threadIdx.x;
@@ -478,7 +499,8 @@ __device__ __forceinline__ void complete_body(
     };
     T acc = T(0);
     auto process_row = [&](const Row &r, int node) {
-        T xh = half_step<V, NEST>(r.x, NEST ? r.u : r.x, r.g, gamma, mom, u + (size_t)node * ld + off);
+        T xh = half_step<V, NEST>(r.x, NEST ? r.u : r.x, r.g, hp, u + (size_t)node * ld + off,
+                                  hp.wd_mode == 2 ? hp.w_old[node] : 1.0f);
         T term = p * xh;
         acc = acc + term;
     };
@@ -508,11 +530,11 @@ template <int V, bool NEST, bool ZOUT>
 __global__ __launch_bounds__(kOpBlock) void k_step_complete(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w, int n,
-    size_t ld, size_t col0, long ncols, float p, float gamma, float mom)
+    size_t ld, size_t col0, long ncols, float p, Hyper hp)
 {
     const bool full = ((long)blockIdx.x + 1) * kOpBlock <= ncols;
 #define SGP_COMPLETE_CALL(DIV, MASKED) \
-    complete_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, p, gamma, mom)
+    complete_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, n, ld, col0, ncols, p, hp)
     if (ZOUT && *unit_w == 0) {
         if (full) SGP_COMPLETE_CALL(true, false);
         else SGP_COMPLETE_CALL(true, true);
@@ -540,7 +562,7 @@ constexpr int kDelayCols = SGP_DELAY_COLS;     // 128-bit column groups per work
 template <int V, bool NEST, int C, int M>
 struct DelayRegs {
     typename vec_of<V>::type x[C], u[C], g[C], m[M > 0 ? M : 1][C];
-    float w;
+    float w, wo;
     int node;
 };
 
@@ -549,7 +571,7 @@ __device__ __forceinline__ void delay_body(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const float *__restrict__ msg_prev,
     float *__restrict__ msg_cur, int n, size_t ld, size_t col0, long ncols,
-    const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
+    const int *__restrict__ tab_prev, int S, float p, Hyper hp)
 {
     typedef typename vec_of<V>::type T;
     constexpr int C = kDelayCols;
@@ -568,6 +590,7 @@ __device__ __forceinline__ void delay_body(
     auto load_row = [&](DelayRegs<V, NEST, C, M> &r, int node) {
         r.node = node;
         r.w = (ZOUT && DIV) ? w[node] : 1.0f;
+        r.wo = hp.wd_mode == 2 ? hp.w_old[node] : 1.0f;
         const size_t row = (size_t)node * ld;
 #pragma unroll
         for (int j = 0; j < C; ++j)
@@ -599,7 +622,7 @@ __device__ __forceinline__ void delay_body(
         for (int j = 0; j < C; ++j)
             if (live[j]) {
                 const size_t a = row + off[j];
-                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], gamma, mom, u + a);
+                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], hp, u + a, r.wo);
                 T own = p * xh;
                 st_stream<V>(msg_cur + a, own);
                 T acc = own;
@@ -644,12 +667,12 @@ __global__ __launch_bounds__(kDelayBlock) void k_step_delay(
     float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
     float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w,
     const float *__restrict__ msg_prev, float *__restrict__ msg_cur, int n, size_t ld, size_t col0,
-    long ncols, const int *__restrict__ tab_prev, int S, float p, float gamma, float mom)
+    long ncols, const int *__restrict__ tab_prev, int S, float p, Hyper hp)
 {
     const bool full = ((long)blockIdx.x + 1) * (kDelayBlock * kDelayCols) <= ncols;
 #define SGP_DELAY_CALL(DIV, MASKED)                                                                   \
     delay_body<V, NEST, ZOUT, NM, DIV, MASKED>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols, \
-                                               tab_prev, S, p, gamma, mom)
+                                               tab_prev, S, p, hp)
     if (ZOUT && *unit_w == 0) {
         if (full) SGP_DELAY_CALL(true, false);
         else SGP_DELAY_CALL(true, true);
@@ -663,11 +686,12 @@ __global__ __launch_bounds__(kDelayBlock) void k_step_delay(
 // Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
 // One block; every work-item reads before anyone writes.
 __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p,
-                        int *__restrict__ unit_w, int biased)
+                        int *__restrict__ unit_w, int biased, float *__restrict__ w_old)
 {
     int i = threadIdx.x;
     float acc = 0.0f;
     if (i < n) {
+        w_old[i] = w[i];
         const int *src = tab + (size_t)i * S;
         acc = p * w[src[0]];
         for (int q = 1; q < S; ++q) {
@@ -681,15 +705,18 @@ __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, flo
 }
 
 // Complete graph: every node ends with the same weight sum_j fl(p * w_j), ascending j.
-__global__ void k_w_complete(float *w, int n, float p, int *__restrict__ unit_w, int biased)
+__global__ void k_w_complete(float *w, int n, float p, int *__restrict__ unit_w, int biased,
+                             float *__restrict__ w_old)
 {
     int i = threadIdx.x;
     float acc = 0.0f;
-    if (i < n)
+    if (i < n) {
+        w_old[i] = w[i];
         for (int j = 0; j < n; ++j) {
             float term = p * w[j];
             acc = acc + term;
         }
+    }
     const int all_one = __syncthreads_and(i >= n || acc == 1.0f);
     if (i < n) w[i] = acc;
     if (i == 0) *unit_w = all_one | biased;
@@ -697,11 +724,12 @@ __global__ void k_w_complete(float *w, int n, float p, int *__restrict__ unit_w,
 
 // Caller-supplied sparse rows: w_i <- sum over the row's entries, in the order given, of weight * w_j.
 __global__ void k_w_custom(float *w, int n, const int *__restrict__ tab, const float *__restrict__ tabw,
-                           int S, int *__restrict__ unit_w, int biased)
+                           int S, int *__restrict__ unit_w, int biased, float *__restrict__ w_old)
 {
     int i = threadIdx.x;
     float acc = 0.0f;
     if (i < n) {
+        w_old[i] = w[i];
         bool any = false;
         for (int q = 0; q < S; ++q) {
             const int j = tab[(size_t)i * S + q];
@@ -717,9 +745,11 @@ __global__ void k_w_custom(float *w, int n, const int *__restrict__ tab, const f
 }
 
 // Iteration without communication: the weights stay, only the flag is refreshed.
-__global__ void k_w_keep(const float *__restrict__ w, int n, int *__restrict__ unit_w, int biased)
+__global__ void k_w_keep(const float *__restrict__ w, int n, int *__restrict__ unit_w, int biased,
+                         float *__restrict__ w_old)
 {
     int i = threadIdx.x;
+    if (i < n) w_old[i] = w[i];
     const int all_one = __syncthreads_and(i >= n || w[i] == 1.0f);
     if (i == 0) *unit_w = all_one | biased;
 }
@@ -728,11 +758,12 @@ __global__ void k_w_keep(const float *__restrict__ w, int n, int *__restrict__ u
 // messages (pre-weighted p*w_j) in ascending sender index; the share is also the new message.
 __global__ void k_w_delay(float *w, const float *__restrict__ msgw_prev, float *__restrict__ msgw_cur,
                           int n, const int *__restrict__ tab_prev, int S, float p,
-                          int *__restrict__ unit_w, int biased)
+                          int *__restrict__ unit_w, int biased, float *__restrict__ w_old)
 {
     int i = threadIdx.x;
     float own = 0.0f, acc = 0.0f;
     if (i < n) {
+        w_old[i] = w[i];
         own = p * w[i];
         acc = own;
         if (tab_prev) {
@@ -997,6 +1028,9 @@ struct sgp_handle {
     int *d_cidx;        // [n][cS] senders, -1 = padding
     float *d_cw;        // [n][cS] weights
     int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
+    float *d_w_old;     // [n] the weights before the latest update (weight decay on x / w)
+    float wd;           // weight decay coefficient, 0 = off
+    bool wd_on_x;       // decay acts on the numerator instead of the de-biased parameters
     float *d_partial;   // [(n+1)][G] partial sums of the statistics
     float *d_partial_f; // [(n+1)][Gf] partial sums written by the fused step+statistics kernel
     size_t partial_f_elems;
@@ -1090,6 +1124,7 @@ int ensure_device(sgp_handle *h)
 
     h->G = kStatsGridMax;
     e = hipMalloc(&h->d_unit_w, sizeof(int));
+    if (e == hipSuccess) e = hipMalloc(&h->d_w_old, (size_t)n * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&h->d_sums,
                                        (size_t)std::max(n + 1, kSlotSumBlocks * (kStatsCache + 1)) * sizeof(double));
@@ -1120,6 +1155,7 @@ void release_device(sgp_handle *h)
     if (h->d_cidx) (void)hipFree(h->d_cidx);
     if (h->d_cw) (void)hipFree(h->d_cw);
     if (h->d_unit_w) (void)hipFree(h->d_unit_w);
+    if (h->d_w_old) (void)hipFree(h->d_w_old);
     if (h->d_partial) (void)hipFree(h->d_partial);
     if (h->d_partial_f) (void)hipFree(h->d_partial_f);
     if (h->d_sums) (void)hipFree(h->d_sums);
@@ -1139,7 +1175,8 @@ struct StepArgs {
     const int *unit_w;
     int n;
     size_t ld;
-    float p, gamma, mom;
+    float p;
+    Hyper hp;
     hipStream_t stream;
 };
 
@@ -1149,7 +1186,7 @@ void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
     hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
                        dim3(kOpBlock), SGP_OP_DYNLDS,
                        a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
-                       len, a.p, a.gamma, a.mom);
+                       len, a.p, a.hp);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -1159,10 +1196,10 @@ void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, c
     dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
     if (tabw)
         hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, true>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
     else
         hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, false>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.gamma, a.mom);
+                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -1170,7 +1207,7 @@ void launch_complete(const StepArgs &a, size_t col0, long ncols)
 {
     hipLaunchKernelGGL((k_step_complete<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
                        0, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, a.p,
-                       a.gamma, a.mom);
+                       a.hp);
 }
 
 template <int V, bool NEST, bool ZOUT>
@@ -1182,19 +1219,19 @@ void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_p
     if (nm == 0)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.gamma, a.mom);
+                           a.p, a.hp);
     else if (nm == 1)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.gamma, a.mom);
+                           a.p, a.hp);
     else if (nm == 2)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.gamma, a.mom);
+                           a.p, a.hp);
     else
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.gamma, a.mom);
+                           a.p, a.hp);
 }
 
 // Calls f.template operator()<NEST, ZOUT>() for the run-time pair of flags.
@@ -1321,6 +1358,14 @@ int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight,
     return SGP_OK;
 }
 
+int sgp_set_weight_decay(sgp_handle *h, float weight_decay, int on_numerator)
+{
+    if (!h || !(weight_decay >= 0.0f)) return SGP_ERR_INVALID_ARG;
+    h->wd = weight_decay;
+    h->wd_on_x = on_numerator != 0;
+    return SGP_OK;
+}
+
 int sgp_set_biased(sgp_handle *h, int biased)
 {
     if (!h) return SGP_ERR_INVALID_ARG;
@@ -1425,7 +1470,9 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
 
-    StepArgs a{x, m, z_out, g, w, h->d_unit_w, n, (size_t)h->ld, s.p, gamma, momentum, st};
+    const bool decay = h->wd != 0.0f;
+    const Hyper hp{gamma, momentum, h->wd, !decay ? 0 : (h->wd_on_x || h->biased) ? 1 : 2, h->d_w_old};
+    StepArgs a{x, m, z_out, g, w, h->d_unit_w, n, (size_t)h->ld, s.p, hp, st};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
 
@@ -1444,7 +1491,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     if (!sending) {
         // between two communication rounds: a local step, x <- xh, w unchanged (Alg. 2, else branch
         // of the send test), which is the one-peer walk with n cycles of length 1 and weight 1
-        hipLaunchKernelGGL(k_w_keep, dim3(1), dim3(wblock), 0, st, w, n, h->d_unit_w, (int)h->biased);
+        hipLaunchKernelGGL(k_w_keep, dim3(1), dim3(wblock), 0, st, w, n, h->d_unit_w, (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         StepArgs al = a;
         al.p = 1.0f;
@@ -1457,7 +1504,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         StepArgs ac = a;
         ac.p = 1.0f / (float)n;
         hipLaunchKernelGGL(k_w_complete, dim3(1), dim3(wblock), 0, st, w, n, ac.p, h->d_unit_w,
-                           (int)h->biased);
+                           (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0) launch_complete<4, NEST, ZOUT>(ac, 0, cols4);
@@ -1465,7 +1512,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         });
     } else if (custom) {
         hipLaunchKernelGGL(k_w_custom, dim3(1), dim3(wblock), 0, st, w, n, h->d_cidx, h->d_cw, h->cS,
-                           h->d_unit_w, (int)h->biased);
+                           h->d_unit_w, (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS);
@@ -1474,7 +1521,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     } else if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
         hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w,
-                           (int)h->biased);
+                           (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         if (!gather) {
             const int hop = s.distinct ? s.uniq[0] % n : 0;
@@ -1493,12 +1540,12 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
                 }
                 if (nest)
                     hipLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
-                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, gamma,
-                                       momentum, h->d_partial_f);
+                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, hp,
+                                       h->d_partial_f);
                 else
                     hipLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
-                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, gamma,
-                                       momentum, h->d_partial_f);
+                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, hp,
+                                       h->d_partial_f);
                 fused->G = (int)Gf;
                 fused->hop = hop;
                 fused->len = len;
@@ -1521,7 +1568,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         }
         const int cur = h->cur, prv = cur ^ 1;
         hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
-                           n, tab_prev, S, s.p, h->d_unit_w, (int)h->biased);
+                           n, tab_prev, S, s.p, h->d_unit_w, (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0)
