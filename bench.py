@@ -40,13 +40,16 @@ def algorithmic_bytes_per_update(wl) -> float:
 
 def read_traffic(workload_name):
     """HBM bytes per launch of the step kernel measured with hardware counters, if a summary for
-    this workload has been committed (profiles/step_kernel_<workload>_pmc.txt)."""
-    path = os.path.join(ROOT, "profiles", "step_kernel_%s_pmc.txt" % workload_name)
-    try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
-    except OSError:
-        return None
+    this workload has been committed (profiles/step_kernel_<workload>_pmc.txt or ..._<workload>.txt)."""
+    for name in ("step_kernel_%s_pmc.txt", "step_kernel_%s.txt"):
+        path = os.path.join(ROOT, "profiles", name % workload_name)
+        try:
+            m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        except OSError:
+            continue
+        if m:
+            return float(m.group(1))
+    return None
 
 
 def cpu_baseline(wl, budget_s=15.0):
