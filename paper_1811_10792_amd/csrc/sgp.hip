@@ -40,6 +40,9 @@
 #ifndef SGP_DELAY_COLS
 #define SGP_DELAY_COLS 2
 #endif
+#ifndef SGP_DELAY_WINDOW
+#define SGP_DELAY_WINDOW 1   // two-peer overlap: walk with the stride of the two hops (0: table walk)
+#endif
 #ifndef SGP_NT_LOAD
 #define SGP_NT_LOAD 1
 #endif
@@ -683,6 +686,167 @@ __global__ __launch_bounds__(kDelayBlock) void k_step_delay(
 #undef SGP_DELAY_CALL
 }
 
+// ------------------------------------------------------------------------------------------
+// Overlap step with exactly two messages per receiver (two out-peers): receiver i hears from
+// ja = i - ha and jb = i - hb (mod n), the previous round's hops.  Walking the receivers with the
+// stride hb - ha makes jb of one row equal to ja of the row before, so each message row is loaded
+// once and handed on in registers, instead of being fetched by both of its receivers (the table
+// driven kernel above fetched 2-24 % more than the algorithmic bytes, depending on how far apart
+// in the ascending walk the two receivers of a message are).  The row that opens a cycle of the
+// stride lacks its second message until the cycle closes; it is parked like the cycle-opening
+// node of the one-peer walk, so that every row issues the same loads and stores.
+// The sum keeps the order of the dense row: own share, then the two messages in ascending sender.
+// ------------------------------------------------------------------------------------------
+template <int V, bool NEST, bool ZOUT, bool DIV, bool MASKED>
+__device__ __forceinline__ void delay2_body(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const float *__restrict__ msg_prev,
+    float *__restrict__ msg_cur, int n, size_t ld, size_t col0, long ncols, int ha, int hb,
+    int stride, int len, float p, Hyper hp)
+{
+    typedef typename vec_of<V>::type T;
+    constexpr int C = kDelayCols;
+    const long cbase = (long)blockIdx.x * (kDelayBlock * C) + threadIdx.x;
+    size_t off[C];
+    bool live[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        long c = cbase + (long)j * kDelayBlock;
+        live[j] = !MASKED || c < ncols;
+        off[j] = col0 + (size_t)(live[j] ? c : 0) * V;
+    }
+    if (MASKED && !live[0]) return;
+
+    auto load_row = [&](DelayRegs<V, NEST, C, 1> &r, int node) {
+        r.node = node;
+        r.w = (ZOUT && DIV) ? w[node] : 1.0f;
+        r.wo = hp.wd_mode == 2 ? hp.w_old[node] : 1.0f;
+        const size_t row = (size_t)node * ld;
+        int ja = node - ha;
+        if (ja < 0) ja += n;
+        const size_t mrow = (size_t)ja * ld;
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                r.x[j] = ld_stream<V>(x + row + off[j]);
+                if (NEST) r.u[j] = ld_stream<V>(u + row + off[j]);
+                r.g[j] = ld_stream<V>(g + row + off[j]);
+                r.m[0][j] = ld_stream<V>(msg_prev + mrow + off[j]);
+            }
+    };
+
+    T prev_ma[C], first_own[C], first_ma[C], parked[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) prev_ma[j] = first_own[j] = first_ma[j] = parked[j] = T(0);
+    int first_node = 0, parked_node = 0;
+    float first_w = 1.0f, parked_w = 1.0f;
+    int ppos = 0;
+
+    auto emit = [&](int node, float wi, const T (&xn)[C]) {
+        const size_t row = (size_t)node * ld;
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+            if (live[j]) {
+                st_stream<V>(x + row + off[j], xn[j]);
+                if (ZOUT) st_stream<V>(z + row + off[j], debias_val<V, DIV>(xn[j], wi));
+            }
+    };
+    // own + the two messages, lower sender index first; sender of ma is node - ha, of mb node - hb
+    auto total = [&](int node, T own, T ma, T mb) {
+        int ja = node - ha, jb = node - hb;
+        if (ja < 0) ja += n;
+        if (jb < 0) jb += n;
+        const bool a_first = ja < jb;
+        T s1 = own + (a_first ? ma : mb);
+        return s1 + (a_first ? mb : ma);
+    };
+
+    auto process_row = [&]<bool EMIT>(const DelayRegs<V, NEST, C, 1> &r) {
+        const size_t row = (size_t)r.node * ld;
+        const bool opens = (ppos == 0), closes = (ppos == len - 1);
+        T xn[C];
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            T own = T(0);
+            if (live[j]) {
+                T xh = half_step<V, NEST>(r.x[j], NEST ? r.u[j] : r.x[j], r.g[j], hp, u + row + off[j], r.wo);
+                own = p * xh;
+                st_stream<V>(msg_cur + row + off[j], own);
+            }
+            if (opens) {
+                xn[j] = parked[j];
+                first_own[j] = own;
+                first_ma[j] = r.m[0][j];
+            } else {
+                xn[j] = total(r.node, own, r.m[0][j], prev_ma[j]);
+            }
+            prev_ma[j] = r.m[0][j];
+        }
+        const int out_node = opens ? parked_node : r.node;
+        const float out_w = opens ? parked_w : r.w;
+        if (opens) {
+            first_node = r.node;
+            first_w = r.w;
+        }
+        if (closes) {   // the opening row's second message is this row's first one
+#pragma unroll
+            for (int j = 0; j < C; ++j) parked[j] = total(first_node, first_own[j], first_ma[j], prev_ma[j]);
+            parked_node = first_node;
+            parked_w = first_w;
+            ppos = 0;
+        } else {
+            ++ppos;
+        }
+        if (EMIT) emit(out_node, out_w, xn);
+    };
+
+    WalkPos lp{0, 0, 0};
+    DelayRegs<V, NEST, C, 1> ra, rb;
+    load_row(ra, lp.node);
+    lp.advance(n, stride, len);
+    load_row(rb, lp.node);          // n >= 3 here: two distinct peers
+    lp.advance(n, stride, len);
+    process_row.template operator()<false>(ra);
+    int t = 1;                      // rb holds row t; later rows are not loaded yet
+    for (; t + 2 < n; t += 2) {
+        load_row(ra, lp.node);
+        lp.advance(n, stride, len);
+        process_row.template operator()<true>(rb);
+        load_row(rb, lp.node);
+        lp.advance(n, stride, len);
+        process_row.template operator()<true>(ra);
+    }
+    if (t + 1 < n) {
+        load_row(ra, lp.node);
+        process_row.template operator()<true>(rb);
+        process_row.template operator()<true>(ra);
+    } else {
+        process_row.template operator()<true>(rb);
+    }
+    emit(parked_node, parked_w, parked);
+}
+
+template <int V, bool NEST, bool ZOUT>
+__global__ __launch_bounds__(kDelayBlock) void k_step_delay2(
+    float *__restrict__ x, float *__restrict__ u, const float *__restrict__ g,
+    float *__restrict__ z, const float *__restrict__ w, const int *__restrict__ unit_w,
+    const float *__restrict__ msg_prev, float *__restrict__ msg_cur, int n, size_t ld, size_t col0,
+    long ncols, int ha, int hb, int stride, int len, float p, Hyper hp)
+{
+    const bool full = ((long)blockIdx.x + 1) * (kDelayBlock * kDelayCols) <= ncols;
+#define SGP_DELAY2_CALL(DIV, MASKED)                                                                  \
+    delay2_body<V, NEST, ZOUT, DIV, MASKED>(x, u, g, z, w, msg_prev, msg_cur, n, ld, col0, ncols, ha, \
+                                            hb, stride, len, p, hp)
+    if (ZOUT && *unit_w == 0) {
+        if (full) SGP_DELAY2_CALL(true, false);
+        else SGP_DELAY2_CALL(true, true);
+    } else {
+        if (full) SGP_DELAY2_CALL(false, false);
+        else SGP_DELAY2_CALL(false, true);
+    }
+#undef SGP_DELAY2_CALL
+}
+
 // Push-sum weights, blocking form (Alg. 1 line 7): w_i <- sum over sources, ascending, of p*w_j.
 // One block; every work-item reads before anyone writes.
 __global__ void k_w_mix(float *w, int n, const int *__restrict__ tab, int S, float p,
@@ -1212,10 +1376,18 @@ void launch_complete(const StepArgs &a, size_t col0, long ncols)
 
 template <int V, bool NEST, bool ZOUT>
 void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
-                  const int *tab_prev, int S)
+                  const int *tab_prev, int S, int ha, int hb)
 {
     dim3 grid(grid_for(ncols, kDelayBlock * kDelayCols)), block(kDelayBlock);
     const int nm = tab_prev ? S - 1 : 0;
+    if (nm == 2 && SGP_DELAY_WINDOW) {   // two messages: each message row is loaded once
+        const int stride = ((hb - ha) % a.n + a.n) % a.n;
+        const int len = a.n / gcd_int(a.n, stride);
+        hipLaunchKernelGGL((k_step_delay2<V, NEST, ZOUT>), grid, block, 0, a.stream, a.x, a.u, a.g, a.z,
+                           a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, ha, hb, stride, len,
+                           a.p, a.hp);
+        return;
+    }
     if (nm == 0)
         hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
@@ -1562,6 +1734,12 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         }
     } else {
         const int *tab_prev = nullptr;
+        int ha = 0, hb = 0;          // the previous round's hops, when there are exactly two
+        if (h->have_msgs && h->L > 0 && S == 3) {
+            const Schedule sp = make_schedule(n, h->peers, round - 1);
+            ha = sp.uniq[0] % n;
+            hb = sp.uniq[1] % n;
+        }
         if (h->have_msgs && h->L > 0) {
             const int kprev = (int)((round - 1) % h->L);
             tab_prev = h->d_tab + (size_t)kprev * n * S;
@@ -1572,9 +1750,10 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
             if (cols4 > 0)
-                launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S);
+                launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb);
             if (tail > 0)
-                launch_delay<1, NEST, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S);
+                launch_delay<1, NEST, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha,
+                                            hb);
         });
         h->cur = prv;
         h->have_msgs = true;
