@@ -9,7 +9,8 @@
  *   sgpo_mixing_matrix_*   dense P^(k) of the directed exponential graph with uniform weights
  *                          (Appendix A "Definition of P^(k)", Appendix C mixing weights)
  *   sgpo_step_*            one SGP iteration, Alg. 1 / Alg. 3, as the dense product of
- *                          eq. "UpdateRule" applied per coordinate
+ *                          eq. "UpdateRule" applied per coordinate; optionally with weight
+ *                          decay, or with Adam as the local step (hyperparameter appendix)
  *   sgpo_step_delay1_*     one iteration of 1-overlap SGP, Alg. 2 with tau = 1
  *   sgpo_step_osgp_*       one iteration of tau-overlap SGP, Alg. 2 with tau >= 1, and the
  *                          biased ablation that skips the de-bias
@@ -40,15 +41,19 @@
 
 #define REAL double
 #define SFX _f64
+#define SQRT sqrt
 #include "sgp_oracle_impl.inc"
 #undef REAL
 #undef SFX
+#undef SQRT
 
 #define REAL float
 #define SFX _f32
+#define SQRT sqrtf
 #include "sgp_oracle_impl.inc"
 #undef REAL
 #undef SFX
+#undef SQRT
 
 /* Threads used by the coordinate loops (results do not depend on it). */
 void sgpo_set_threads(int t)

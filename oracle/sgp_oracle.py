@@ -50,14 +50,14 @@ def _load():
                 f.argtypes = [i32, i32, i64, vp]
                 f.restype = None
                 f = getattr(lib, "sgpo_step" + sfx)
-                f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, real, i32]
+                f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, real, i32, vp, vp]
                 f.restype = i32
                 f = getattr(lib, "sgpo_step_delay1" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, vp, vp, vp, i32]
                 f.restype = i32
                 f = getattr(lib, "sgpo_step_osgp" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, real, real, i32, i32, i64, i32,
-                              vp, vp, vp, vp, real, i32]
+                              vp, vp, vp, vp, real, i32, vp, vp]
                 f.restype = i32
                 f = getattr(lib, "sgpo_debias" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp]
@@ -102,14 +102,24 @@ def mixing_matrix(n: int, peers: int, k: int, dtype=np.float64) -> np.ndarray:
     return P
 
 
-def step(P, x, w, u, g, gamma, m, nesterov=True, wd=0.0, wd_on_x=False):
+def adam_params(beta1, beta2, eps, t, dtype):
+    """The seven Adam scalars in the working precision: beta1, 1 - beta1, beta2, 1 - beta2 and the
+    bias corrections 1 - beta1^t, 1 - beta2^t (formed in double, then rounded), eps."""
+    dt = np.dtype(dtype).type
+    b1, b2 = dt(beta1), dt(beta2)
+    return np.array([b1, dt(1) - b1, b2, dt(1) - b2, dt(1.0 - float(b1) ** t), dt(1.0 - float(b2) ** t),
+                     dt(eps)], dtype=dtype)
+
+
+def step(P, x, w, u, g, gamma, m, nesterov=True, wd=0.0, wd_on_x=False, adam=None, v=None):
     """One SGP iteration with mixing matrix P (Alg. 1 if nesterov is False, else Alg. 3).
-    Updates x, w (and u) in place and returns z.  wd: weight decay, g + wd * z (or wd * x)."""
+    Updates x, w (and u) in place and returns z.  wd: weight decay, g + wd * z (or wd * x).
+    adam: array from adam_params() -> Adam is the local step, u and v hold its two moments."""
     dt = x.dtype
     n, d = x.shape
     z = np.empty_like(x)
     if u is None:
-        if nesterov:
+        if nesterov or adam is not None:
             raise ValueError("momentum needs the buffer u")
         up = None
     else:
@@ -117,7 +127,8 @@ def step(P, x, w, u, g, gamma, m, nesterov=True, wd=0.0, wd_on_x=False):
     rc = getattr(_load(), "sgpo_step" + _sfx(dt))(
         n, d, _chk(P, dt, (n, n)), _chk(x, dt, (n, d)), _chk(w, dt, (n,)), up,
         _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)),
-        float(wd), int(bool(wd_on_x)))
+        float(wd), int(bool(wd_on_x)), None if adam is None else _chk(v, dt, (n, d)),
+        None if adam is None else _chk(adam, dt, (7,)))
     if rc != 0:
         raise MemoryError("oracle step failed")
     return z
@@ -168,7 +179,7 @@ class OsgpState:
 
 
 def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, biased=False,
-              wd=0.0, wd_on_x=False):
+              wd=0.0, wd_on_x=False, adam=None, v=None):
     """Iteration k of tau-overlap SGP (Alg. 2): sends at k % tau == 0 with matrix P, receives what
     was sent tau iterations ago; biased=True returns z = x (the ablation without push-sum weight)."""
     dt = x.dtype
@@ -182,7 +193,8 @@ def step_osgp(P, x, w, u, g, gamma, m, state: OsgpState, k: int, nesterov=True, 
         _chk(g, dt, (n, d)), z.ctypes.data, float(gamma), float(m), int(bool(nesterov)),
         int(state.tau), int(k), int(bool(biased)), _chk(state.xh_sent, dt, (n, d)),
         _chk(state.w_sent, dt, (n,)), _chk(state.P_sent, dt, (n, n)), state.arrival.ctypes.data,
-        float(wd), int(bool(wd_on_x)))
+        float(wd), int(bool(wd_on_x)), None if adam is None else _chk(v, dt, (n, d)),
+        None if adam is None else _chk(adam, dt, (7,)))
     if rc != 0:
         raise RuntimeError("oracle step_osgp failed (%d)" % rc)
     return z

@@ -332,6 +332,65 @@ def test_weight_decay_acts_on_z_or_on_x():
     assert np.abs(xa - xb).max() > 1e-4
 
 
+@pytest.mark.parametrize("wd", [0.0, 0.01])
+def test_adam_local_step_is_the_library_optimizer(wd):
+    # every node runs torch.optim.Adam on its numerator with the gradient it was handed; the mix
+    # is then the dense product with P (per coordinate)
+    rng = np.random.default_rng(43)
+    n, d, gamma, b1, b2, eps = 4, 6, 0.01, 0.9, 0.98, 1e-8
+    P = _random_column_stochastic(rng, n)
+    x = rng.standard_normal((n, d))
+    w = np.ones(n)
+    m1, m2 = np.zeros((n, d)), np.zeros((n, d))
+    params = [torch.tensor(x[i].copy(), requires_grad=True) for i in range(n)]
+    opts = [torch.optim.Adam([p], lr=gamma, betas=(b1, b2), eps=eps, weight_decay=wd) for p in params]
+    for t in range(1, 7):
+        g = rng.standard_normal((n, d))
+        for i in range(n):
+            with torch.no_grad():
+                params[i].copy_(torch.tensor(x[i]))       # the optimiser steps on the numerator
+            params[i].grad = torch.tensor(g[i].copy())
+            opts[i].step()
+        xh = np.stack([p.detach().numpy() for p in params])
+        w_ref = P @ w
+        z = O.step(P, x, w, m1, g, gamma, 0.0, nesterov=False, wd=wd, wd_on_x=True,
+                   adam=O.adam_params(b1, b2, eps, t, F64), v=m2)
+        assert np.abs(x - P @ xh).max() < 1e-12
+        assert np.abs(w - w_ref).max() < 1e-15
+        assert np.abs(z - (P @ xh) / w_ref[:, None]).max() < 1e-12
+        for i in range(n):
+            st = opts[i].state[params[i]]
+            assert np.abs(m1[i] - st["exp_avg"].numpy()).max() < 1e-14
+            assert np.abs(m2[i] - st["exp_avg_sq"].numpy()).max() < 1e-14
+
+
+def test_adam_under_overlap_equals_adam_then_delayed_mix():
+    # the overlap oracle with Adam = the same local step followed by the delayed mix: compare with
+    # the blocking oracle's local step (P = I gives xh) fed through the tau = 2 message schedule
+    rng = np.random.default_rng(44)
+    n, d, tau = 5, 3, 2
+    x = rng.standard_normal((n, d))
+    w = np.ones(n)
+    xa, wa, ua, va = x.copy(), w.copy(), np.zeros((n, d)), np.zeros((n, d))
+    xb, wb, ub, vb = x.copy(), w.copy(), np.zeros((n, d)), np.zeros((n, d))
+    sa, sb = O.OsgpState(n, d, F64, tau), O.OsgpState(n, d, F64, tau)
+    for k in range(7):
+        g = rng.standard_normal((n, d))
+        ad = O.adam_params(0.9, 0.999, 1e-8, k + 1, F64)
+        P = O.mixing_matrix(n, 2, k // tau)
+        za = O.step_osgp(P, xa, wa, ua, g, 0.05, 0.0, sa, k, nesterov=False, adam=ad, v=va)
+        # reference: local Adam step alone (identity mixing), then plain SGD-free overlap step with
+        # gamma = 0 on the result
+        wtmp = np.ones(n)
+        xh = xb.copy()
+        O.step(np.eye(n), xh, wtmp, ub, g, 0.05, 0.0, nesterov=False, adam=ad, v=vb)
+        xb[:] = xh
+        zb = O.step_osgp(P, xb, wb, None, np.zeros((n, d)), 0.0, 0.0, sb, k, nesterov=False)
+        assert np.abs(xa - xb).max() < 1e-14 and np.abs(wa - wb).max() < 1e-15
+        assert np.abs(za - zb).max() < 1e-13
+        assert np.array_equal(ua, ub) and np.array_equal(va, vb)
+
+
 def test_zero_momentum_reduces_alg3_to_alg1():
     rng = np.random.default_rng(16)
     for dtype in (F64, F32):
