@@ -174,6 +174,24 @@ int sgp_reset(sgp_handle *h);
 int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
              float gamma, float momentum, int64_t k, void *stream);
 
+/*
+ * One SGP iteration with Adam as the local optimiser (the machine-translation runs combine SGP with
+ * the Adam preconditioner; the paper prints no formulas, so Adam is taken as published by Kingma
+ * and Ba and applied to the numerator with the gradient evaluated at z):
+ *     m1_i <- beta1 m1_i + (1 - beta1) g_i ,   m2_i <- beta2 m2_i + (1 - beta2) g_i^2
+ *     xh_i  = x_i - gamma * (m1_i / (1 - beta1^t)) / (sqrt(m2_i / (1 - beta2^t)) + eps)
+ * followed by the same mix, weight update and de-bias as sgp_step, for every topology and delay.
+ *   m1, m2 [n][ld] device, in/out : first and second moment (start at zero); m2 must not overlap
+ *                                   any other array
+ *   t >= 1                        : Adam's step count (bias corrections are formed in double and
+ *                                   rounded once to float)
+ * Other arguments, layout, overlap-mode sequencing and errors as for sgp_step; weight decay set by
+ * sgp_set_weight_decay is added to g_i first (L2 form).  32 bytes of HBM traffic per node-parameter
+ * (40 in overlap mode).
+ */
+int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const float *g, float *z_out,
+                  float gamma, float beta1, float beta2, float eps, int64_t t, int64_t k, void *stream);
+
 /* z_i = x_i / w_i for all nodes (last line of Alg. 1); x [n][ld], w [n], z [n][ld] device.
  * Used for z^(0) and whenever sgp_step was called with z_out == NULL. */
 int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *stream);

@@ -30,7 +30,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
-           "sgp_set_mixing", "sgp_set_weight_decay")
+           "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam")
 
 
 class SgpError(RuntimeError):
@@ -76,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_destroy.argtypes = [vp]
     lib.sgp_reset.argtypes = [vp]
     lib.sgp_step.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, vp]
+    lib.sgp_step_adam.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, i64, vp]
     lib.sgp_debias.argtypes = [vp, vp, vp, vp, vp]
     lib.sgp_consensus_stats.argtypes = [vp, vp, vp, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_peer_schedule.argtypes = [vp, i64, vp, vp, ctypes.POINTER(f32)]
@@ -178,6 +179,15 @@ class SGP:
         self._expect(w, "w", rows_only=True)
         _check(self._lib.sgp_step(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), _ptr(z_out),
                                   gamma, momentum, k, _stream(stream)), "sgp_step")
+
+    def step_adam(self, x, w, m1, m2, g, z_out, gamma: float, beta1: float, beta2: float, eps: float,
+                  t: int, k: int, stream=None) -> None:
+        """One iteration with Adam as the local optimiser (m1, m2: its two moments, t: its step count)."""
+        for tt, name in ((x, "x"), (m1, "m1"), (m2, "m2"), (g, "g"), (z_out, "z_out")):
+            self._expect(tt, name)
+        self._expect(w, "w", rows_only=True)
+        _check(self._lib.sgp_step_adam(self._h, _ptr(x), _ptr(w), _ptr(m1), _ptr(m2), _ptr(g), _ptr(z_out),
+                                       gamma, beta1, beta2, eps, t, k, _stream(stream)), "sgp_step_adam")
 
     def step_stats(self, x, w, m, g, z_out, gamma: float, momentum: float, k: int,
                    per_node: bool = False, stream=None) -> Stats:

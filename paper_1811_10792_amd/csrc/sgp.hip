@@ -25,6 +25,7 @@
 //   sgp.hip                 handle, launchers, C ABI
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -250,37 +251,37 @@ struct StepArgs {
     hipStream_t stream;
 };
 
-template <int V, bool NEST, bool ZOUT>
+template <int V, int OPT, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
-    hipLaunchKernelGGL((k_step_one_peer<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
+    hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
                        dim3(kOpBlock), SGP_OP_DYNLDS,
                        a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
                        len, a.p, a.hp);
 }
 
-template <int V, bool NEST, bool ZOUT>
+template <int V, int OPT, bool ZOUT>
 void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S)
 {
     size_t lds = (size_t)a.n * kGatherBlock * V * sizeof(float);
     dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
     if (tabw)
-        hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, true>), grid, block, lds, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_gather<V, OPT, ZOUT, true>), grid, block, lds, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
     else
-        hipLaunchKernelGGL((k_step_gather<V, NEST, ZOUT, false>), grid, block, lds, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_gather<V, OPT, ZOUT, false>), grid, block, lds, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
 }
 
-template <int V, bool NEST, bool ZOUT>
+template <int V, int OPT, bool ZOUT>
 void launch_complete(const StepArgs &a, size_t col0, long ncols)
 {
-    hipLaunchKernelGGL((k_step_complete<V, NEST, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
+    hipLaunchKernelGGL((k_step_complete<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
                        0, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, a.p,
                        a.hp);
 }
 
-template <int V, bool NEST, bool ZOUT>
+template <int V, int OPT, bool ZOUT>
 void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
                   const int *tab_prev, int S, int ha, int hb)
 {
@@ -289,39 +290,42 @@ void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_p
     if (nm == 2 && SGP_DELAY_WINDOW) {   // two messages: each message row is loaded once
         const int stride = ((hb - ha) % a.n + a.n) % a.n;
         const int len = a.n / gcd_int(a.n, stride);
-        hipLaunchKernelGGL((k_step_delay2<V, NEST, ZOUT>), grid, block, 0, a.stream, a.x, a.u, a.g, a.z,
+        hipLaunchKernelGGL((k_step_delay2<V, OPT, ZOUT>), grid, block, 0, a.stream, a.x, a.u, a.g, a.z,
                            a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, ha, hb, stride, len,
                            a.p, a.hp);
         return;
     }
     if (nm == 0)
-        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
     else if (nm == 1)
-        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
     else if (nm == 2)
-        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
     else
-        hipLaunchKernelGGL((k_step_delay<V, NEST, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
 }
 
-// Calls f.template operator()<NEST, ZOUT>() for the run-time pair of flags.
+// Calls f.template operator()<OPT, ZOUT>() for the run-time optimiser and z flag.
 template <typename F>
-void dispatch_flags(bool nest, bool zout, F &&f)
+void dispatch_flags(int opt, bool zout, F &&f)
 {
-    if (nest) {
-        if (zout) f.template operator()<true, true>();
-        else f.template operator()<true, false>();
+    if (opt == kOptAdam) {
+        if (zout) f.template operator()<kOptAdam, true>();
+        else f.template operator()<kOptAdam, false>();
+    } else if (opt == kOptNesterov) {
+        if (zout) f.template operator()<kOptNesterov, true>();
+        else f.template operator()<kOptNesterov, false>();
     } else {
-        if (zout) f.template operator()<false, true>();
-        else f.template operator()<false, false>();
+        if (zout) f.template operator()<kOptSgd, true>();
+        else f.template operator()<kOptSgd, false>();
     }
 }
 
@@ -511,16 +515,30 @@ struct FusedStats {
 // One iteration; with fused != NULL the caller wants the statistics of z^(k+1) as well: when the
 // fused kernel applies, it is used and *fused describes the partial table it left in
 // h->d_partial_f, otherwise fused->G stays 0 and the caller runs the stand-alone statistics pass.
+// Adam's scalars as sgp_step_adam hands them over (NULL: SGD / Nesterov).
+struct AdamArgs {
+    float *v2;
+    float beta1, beta2, eps;
+    int64_t t;
+};
+
 static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
-                     float gamma, float momentum, int64_t k, void *stream, FusedStats *fused)
+                     float gamma, float momentum, int64_t k, void *stream, FusedStats *fused,
+                     const AdamArgs *adam = nullptr)
 {
     if (!h || !x || !w || !g || k < 0) return SGP_ERR_INVALID_ARG;
-    const bool nest = momentum != 0.0f;
+    const int opt = adam ? kOptAdam : momentum != 0.0f ? kOptNesterov : kOptSgd;
+    const bool nest = opt != kOptSgd;          // the momentum / first-moment array is in use
     if (nest && !m) return SGP_ERR_INVALID_ARG;
+    if (adam && (!adam->v2 || adam->t < 1 || !(adam->beta1 >= 0.0f && adam->beta1 < 1.0f) ||
+                 !(adam->beta2 >= 0.0f && adam->beta2 < 1.0f) || !(adam->eps >= 0.0f)))
+        return SGP_ERR_INVALID_ARG;
     if (!aligned4(x) || !aligned4(w) || !aligned4(g) || (nest && !aligned4(m)) ||
-        (z_out && !aligned4(z_out)))
+        (adam && !aligned4(adam->v2)) || (z_out && !aligned4(z_out)))
         return SGP_ERR_ALIGNMENT;
-    if (z_out && (z_out == x || z_out == g || (nest && z_out == m))) return SGP_ERR_INVALID_ARG;
+    if (z_out && (z_out == x || z_out == g || (nest && z_out == m) || (adam && z_out == adam->v2)))
+        return SGP_ERR_INVALID_ARG;
+    if (adam && (adam->v2 == x || adam->v2 == m || adam->v2 == g)) return SGP_ERR_INVALID_ARG;
     if (h->delay && h->last_k >= 0 && k != h->last_k + 1) return SGP_ERR_SEQUENCE;
 
     // tau >= 2: nodes communicate at the iterations with k mod tau == 0 only, and the schedule
@@ -542,14 +560,29 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m)) &&
-               (!z_out || aligned16(z_out));
+               (!adam || aligned16(adam->v2)) && (!z_out || aligned16(z_out));
     if (gather && n > 64) vec = false;   // keep the LDS stash within 64 KiB
     const long cols4 = vec ? (long)(h->d / 4) : 0;             // full 128-bit groups
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
 
     const bool decay = h->wd != 0.0f;
-    const Hyper hp{gamma, momentum, h->wd, !decay ? 0 : (h->wd_on_x || h->biased) ? 1 : 2, h->d_w_old};
+    Hyper hp{};
+    hp.gamma = gamma;
+    hp.mom = momentum;
+    hp.wd = h->wd;
+    hp.wd_mode = !decay ? 0 : (h->wd_on_x || h->biased) ? 1 : 2;
+    hp.w_old = h->d_w_old;
+    if (adam) {   // bias corrections in double, rounded once
+        hp.v2 = adam->v2;
+        hp.beta1 = adam->beta1;
+        hp.c1 = 1.0f - adam->beta1;
+        hp.beta2 = adam->beta2;
+        hp.c2 = 1.0f - adam->beta2;
+        hp.bc1 = (float)(1.0 - std::pow((double)adam->beta1, (double)adam->t));
+        hp.bc2 = (float)(1.0 - std::pow((double)adam->beta2, (double)adam->t));
+        hp.eps = adam->eps;
+    }
     StepArgs a{x, m, z_out, g, w, h->d_unit_w, n, (size_t)h->ld, s.p, hp, st};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
@@ -573,9 +606,9 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         StepArgs al = a;
         al.p = 1.0f;
-        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-            if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(al, 0, cols4, 0, 1);
-            if (tail > 0) launch_one_peer<1, NEST, ZOUT>(al, tail0, tail, 0, 1);
+        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+            if (cols4 > 0) launch_one_peer<4, OPT, ZOUT>(al, 0, cols4, 0, 1);
+            if (tail > 0) launch_one_peer<1, OPT, ZOUT>(al, tail0, tail, 0, 1);
         });
         h->last_k = k;
     } else if (complete) {
@@ -584,17 +617,17 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         hipLaunchKernelGGL(k_w_complete, dim3(1), dim3(wblock), 0, st, w, n, ac.p, h->d_unit_w,
                            (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
-        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-            if (cols4 > 0) launch_complete<4, NEST, ZOUT>(ac, 0, cols4);
-            if (tail > 0) launch_complete<1, NEST, ZOUT>(ac, tail0, tail);
+        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+            if (cols4 > 0) launch_complete<4, OPT, ZOUT>(ac, 0, cols4);
+            if (tail > 0) launch_complete<1, OPT, ZOUT>(ac, tail0, tail);
         });
     } else if (custom) {
         hipLaunchKernelGGL(k_w_custom, dim3(1), dim3(wblock), 0, st, w, n, h->d_cidx, h->d_cw, h->cS,
                            h->d_unit_w, (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
-        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-            if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS);
-            if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS);
+        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+            if (cols4 > 0) launch_gather<4, OPT, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS);
+            if (tail > 0) launch_gather<1, OPT, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS);
         });
     } else if (h->delay == 0) {
         // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
@@ -605,7 +638,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
             const int len = n / ncyc;
-            if (fused && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
+            if (fused && !adam && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
                 const unsigned Gf = grid_for(cols4, kStatsStepBlock);
                 const size_t need = (size_t)(kStatsCache + 1) * Gf;
                 if (need > h->partial_f_elems) {
@@ -616,7 +649,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
                     if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
                     h->partial_f_elems = need;
                 }
-                if (nest)
+                if (opt == kOptNesterov)
                     hipLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
                                        z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, hp,
                                        h->d_partial_f);
@@ -628,14 +661,14 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
                 fused->hop = hop;
                 fused->len = len;
             } else
-            dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-                if (cols4 > 0) launch_one_peer<4, NEST, ZOUT>(a, 0, cols4, hop, len);
-                if (tail > 0) launch_one_peer<1, NEST, ZOUT>(a, tail0, tail, hop, len);
+            dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+                if (cols4 > 0) launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, hop, len);
+                if (tail > 0) launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, hop, len);
             });
         } else {
-            dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
-                if (cols4 > 0) launch_gather<4, NEST, ZOUT>(a, 0, cols4, tab_k, nullptr, S);
-                if (tail > 0) launch_gather<1, NEST, ZOUT>(a, tail0, tail, tab_k, nullptr, S);
+            dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+                if (cols4 > 0) launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab_k, nullptr, S);
+                if (tail > 0) launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab_k, nullptr, S);
             });
         }
     } else {
@@ -654,11 +687,11 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
                            n, tab_prev, S, s.p, h->d_unit_w, (int)h->biased, h->d_w_old);
         if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
-        dispatch_flags(nest, z_out != nullptr, [&]<bool NEST, bool ZOUT>() {
+        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
             if (cols4 > 0)
-                launch_delay<4, NEST, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb);
+                launch_delay<4, OPT, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb);
             if (tail > 0)
-                launch_delay<1, NEST, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha,
+                launch_delay<1, OPT, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha,
                                             hb);
         });
         h->cur = prv;
@@ -677,6 +710,13 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
              float momentum, int64_t k, void *stream)
 {
     return step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, nullptr);
+}
+
+int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const float *g, float *z_out,
+                  float gamma, float beta1, float beta2, float eps, int64_t t, int64_t k, void *stream)
+{
+    const AdamArgs adam{m2, beta1, beta2, eps, t};
+    return step_impl(h, x, w, m1, g, z_out, gamma, 0.0f, k, stream, nullptr, &adam);
 }
 
 // Reduces a partial table to the statistics, copies them to the host and waits.  fused == NULL:
