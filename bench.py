@@ -30,8 +30,10 @@ def algorithmic_bytes_per_update(wl) -> float:
     """HBM bytes the method itself must move per node-parameter: state read once, state written
     once (the gather costs nothing when a work-item owns a coordinate for all nodes)."""
     nest = wl.momentum != 0.0
-    reads = 4 * (2 + (1 if nest else 0))          # x, g, (u)
-    writes = 4 * (2 + (1 if nest else 0))         # x, z, (u)
+    adam = wl.optimizer == "adam"
+    moments = 2 if adam else 1 if nest else 0
+    reads = 4 * (2 + moments)                     # x, g, (u), (second moment)
+    writes = 4 * (2 + moments)                    # x, z, (u), (second moment)
     total = float(reads + writes)
     if wl.delay:                                  # previous messages read, new messages written,
         total += 8.0 / wl.delay                   # at one iteration in every tau
@@ -70,6 +72,8 @@ def cpu_baseline(wl, budget_s=15.0):
     g = syn.normal((n, dslice), wl.grad_std, wl.seed, 4, 0)
     st = O.OsgpState(n, dslice, np.float32, wl.delay) if wl.delay else None
     nest = wl.momentum != 0.0
+    adam = wl.optimizer == "adam"
+    v = np.zeros((n, dslice), np.float32) if adam else None
     steps, t0 = 0, time.perf_counter()
     while True:
         if wl.topology == "complete":
@@ -77,10 +81,11 @@ def cpu_baseline(wl, budget_s=15.0):
         else:
             P = O.mixing_matrix(n, wl.peers, steps // max(1, wl.delay), np.float32)
         if wl.delay:
-            z = O.step_osgp(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, st, steps,
-                            nesterov=nest)
+            z = O.step_osgp(P, x, w, u if (nest or adam) else None, g, wl.gamma, wl.momentum, st, steps,
+                            nesterov=nest, adam=O.adam_params(0.9, 0.98, 1e-8, steps + 1, np.float32) if adam else None, v=v)
         else:
-            z = O.step(P, x, w, u if nest else None, g, wl.gamma, wl.momentum, nesterov=nest)
+            z = O.step(P, x, w, u if (nest or adam) else None, g, wl.gamma, wl.momentum, nesterov=nest,
+                       adam=O.adam_params(0.9, 0.98, 1e-8, steps + 1, np.float32) if adam else None, v=v)
         if wl.stats_each_step:
             O.consensus_stats(z, w)
         steps += 1
@@ -133,6 +138,8 @@ def main():
     U = alloc.floats("u", n, ld).zero_()
     W = torch.ones(n, dtype=torch.float32, device="cuda")
     Z = alloc.floats("z", n, ld)
+    adam = wl.optimizer == "adam"
+    V2 = alloc.floats("v", n, ld).zero_() if adam else None
     pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i, out=alloc.floats("g", n, ld, "g%d" % i))
             for i in range(max(1, args.pool))]
     if wl.delay:
@@ -144,6 +151,9 @@ def main():
     last = None
 
     def one_step(k):
+        if adam:
+            eng.step_adam(X, W, U, V2, pool[k % len(pool)], Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
+            return eng.consensus_stats(Z, W) if do_stats else None
         if do_stats and not args.separate_stats:    # one call: statistics fused into the step kernel
             return eng.step_stats(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma,
                                   wl.momentum, k)
@@ -190,7 +200,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "topology": wl.topology,
                    "peers": wl.peers, "delay": wl.delay,
-                   "momentum": wl.momentum, "gamma": wl.gamma,
+                   "optimizer": wl.optimizer, "momentum": wl.momentum, "gamma": wl.gamma,
                    "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool),
                    "placement": alloc.describe()},
         "roofline": {"bound": "hbm", "kernel": kernel_name,
@@ -202,7 +212,7 @@ def main():
     if last is not None:
         out["consensus_dist_max_last"] = last.dist_max
     eng.close()
-    del X, U, Z, pool, alloc
+    del X, U, Z, V2, pool, alloc
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

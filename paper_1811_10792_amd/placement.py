@@ -193,7 +193,7 @@ class StateAllocator:
     message buffers of overlap mode go with u ("msg0") and with x ("msg1"): a message buffer written
     into the region of z measured 2.5 % slower (17.5 against 17.1 ms at n = 16, d = 213 M)."""
 
-    ROLE_CLASS = {"x": 0, "g": 0, "u": 1, "msg0": 1, "z": 2, "msg1": 0}
+    ROLE_CLASS = {"x": 0, "g": 0, "u": 1, "msg0": 1, "z": 2, "msg1": 0, "v": 2}
 
     def __init__(self, mode: str = "regions", device="cuda"):
         self.device = device

@@ -31,6 +31,7 @@ class Workload:
     x_std: float           # std of the initial x
     stats_each_step: bool = False
     seed: int = 0
+    optimizer: str = "nesterov"   # "nesterov" (momentum 0: plain SGD) or "adam" (beta 0.9 / 0.98, eps 1e-8)
     topology: str = "exp"  # "exp": directed exponential graph; "complete": every entry of P is 1/n
 
 
@@ -52,6 +53,10 @@ WORKLOADS = {
     # configuration 4's shape on the complete graph (the AllReduce-equivalent end of the hybrid schemes)
     "x2_n32_resnet50_complete": Workload("x2_n32_resnet50_complete", 32, 25_557_032, 1, 0, 0.1, 0.9, 50,
                                          "fresh", 1e-3, 0.05, topology="complete"),
+    # configuration 5 with Adam as the local optimiser (what the paper's Transformer runs use)
+    "x3_n16_transformer_2peer_overlap_adam": Workload("x3_n16_transformer_2peer_overlap_adam", 16,
+                                                      213_000_000, 2, 1, 1e-3, 0.0, 20, "fresh", 1e-4, 0.05,
+                                                      optimizer="adam"),
 }
 
 
