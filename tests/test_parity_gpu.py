@@ -324,24 +324,36 @@ def _full_size_spot_check(wl, steps, count=3000):
     cidx = torch.from_numpy(cols).to(DEV)
     xo, uo = host(X[:, cidx]), host(U[:, cidx])
     wo = np.ones(n, np.float32)
-    eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=wl.delay)
+    complete = wl.topology == "complete"
+    adam = wl.optimizer == "adam"
+    eng = sgp.SGP(n, d, ld, topology=1 if complete else 0, peers=wl.peers, delay=wl.delay)
     if wl.delay:
         eng.set_message_buffers(alloc.floats("msg0", n, ld), alloc.floats("msg1", n, ld))
     st = O.OsgpState(n, len(cols), np.float32, wl.delay) if wl.delay else None
+    V2 = alloc.floats("v", n, ld).zero_() if adam else None
+    vo = np.zeros_like(xo) if adam else None
     pad0 = [host(T[:, d:]).copy() for T in (X, U)]
     s_fused = None
     for k in range(steps):
         G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + k, out=Gbuf)
         g = host(G[:, cidx])
-        if wl.stats_each_step:                                 # what the benchmark calls
+        if adam:
+            eng.step_adam(X, W, U, V2, G, Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
+        elif wl.stats_each_step:                               # what the benchmark calls
             s_fused = eng.step_stats(X, W, U, G, Z, wl.gamma, wl.momentum, k, per_node=True)
         else:
             eng.step(X, W, U, G, Z, wl.gamma, wl.momentum, k)
-        P = O.mixing_matrix(n, wl.peers, k // max(1, wl.delay), np.float32)
-        if wl.delay:
-            zo = O.step_osgp(P, xo, wo, uo, g, wl.gamma, wl.momentum, st, k)
+        if complete:
+            P = np.full((n, n), np.float32(1.0) / np.float32(n), dtype=np.float32)
         else:
-            zo = O.step(P, xo, wo, uo, g, wl.gamma, wl.momentum)
+            P = O.mixing_matrix(n, wl.peers, k // max(1, wl.delay), np.float32)
+        kw = dict(nesterov=False, adam=O.adam_params(0.9, 0.98, 1e-8, k + 1, np.float32), v=vo) if adam else {}
+        if wl.delay:
+            zo = O.step_osgp(P, xo, wo, uo, g, wl.gamma, wl.momentum, st, k, **kw)
+        else:
+            zo = O.step(P, xo, wo, uo, g, wl.gamma, wl.momentum, **kw)
+        if adam:
+            same(host(V2[:, cidx]), vo, "%s second moment k=%d" % (wl.name, k))
         same(host(X[:, cidx]), xo, "%s x k=%d" % (wl.name, k))
         same(host(Z[:, cidx]), zo, "%s z k=%d" % (wl.name, k))
         same(host(U[:, cidx]), uo, "%s u k=%d" % (wl.name, k))
@@ -388,3 +400,11 @@ def test_full_size_config5_n16_transformer_two_peer_overlap():
 
 def test_full_size_transformer_two_peer_tau2():
     _full_size_spot_check(syn.WORKLOADS["x1_n16_transformer_2peer_tau2"], steps=5)
+
+
+def test_full_size_resnet50_complete_graph():
+    _full_size_spot_check(syn.WORKLOADS["x2_n32_resnet50_complete"], steps=2)
+
+
+def test_full_size_transformer_two_peer_overlap_adam():
+    _full_size_spot_check(syn.WORKLOADS["x3_n16_transformer_2peer_overlap_adam"], steps=3)
