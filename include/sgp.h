@@ -208,6 +208,18 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
                         double *per_node_dist_host, void *stream);
 
 /*
+ * The same statistics at the measurement point of the figure on parameter deviations: after the
+ * local step and before communication ("just after line 4 in Alg. 1").  Takes the state BEFORE
+ * iteration k and the gradient of iteration k, forms xh_i as sgp_step would (Alg. 1 line 4, or
+ * Alg. 3 lines 4-5 when momentum != 0, weight decay included) and reports the deviations of
+ * xh_i / w_i from their node-wise average.  Nothing is modified: call it before the sgp_step that
+ * consumes the same g.  Reads x, g (and m) once (twice for n > 32).  SYNCHRONISES the stream.
+ */
+int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const float *m, const float *g,
+                        float gamma, float momentum, sgp_stats *host_out, double *per_node_dist_host,
+                        void *stream);
+
+/*
  * sgp_step followed by sgp_consensus_stats of the z^(k+1) it wrote, in one call (Alg. 1 / Alg. 3
  * plus the "Parameter deviations" statistics).  Arguments as in those two calls; z_out and
  * host_out are required.  For one out-peer without delay, n <= 32, d % 4 == 0 and the 128-bit

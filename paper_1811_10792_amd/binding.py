@@ -30,7 +30,8 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_consensus_stats", "sgp_peer_schedule", "sgp_schedule", "sgp_status_string",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
-           "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam")
+           "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
+           "sgp_pregossip_stats")
 
 
 class SgpError(RuntimeError):
@@ -79,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_step_adam.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, i64, vp]
     lib.sgp_debias.argtypes = [vp, vp, vp, vp, vp]
     lib.sgp_consensus_stats.argtypes = [vp, vp, vp, ctypes.POINTER(_CStats), vp, vp]
+    lib.sgp_pregossip_stats.argtypes = [vp, vp, vp, vp, vp, f32, f32, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_peer_schedule.argtypes = [vp, i64, vp, vp, ctypes.POINTER(f32)]
     lib.sgp_schedule.argtypes = [i32, i32, i64, vp, vp, ctypes.POINTER(f32)]
     lib.sgp_status_string.argtypes = [ctypes.c_int]
@@ -219,6 +221,20 @@ class SGP:
         _check(self._lib.sgp_consensus_stats(self._h, _ptr(z), _ptr(w), ctypes.byref(cs),
                                              ctypes.addressof(buf) if per_node else None,
                                              _stream(stream)), "sgp_consensus_stats")
+        return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
+                     cs.argmin, list(buf) if per_node else None)
+
+    def pregossip_stats(self, x, w, m, g, gamma: float, momentum: float, per_node: bool = False,
+                        stream=None) -> Stats:
+        """Statistics of xh / w, the parameters after the local step and before communication."""
+        for t, name in ((x, "x"), (m, "m"), (g, "g")):
+            self._expect(t, name)
+        self._expect(w, "w", rows_only=True)
+        cs = _CStats()
+        buf = (ctypes.c_double * self.n)() if per_node else None
+        _check(self._lib.sgp_pregossip_stats(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), gamma, momentum,
+                                             ctypes.byref(cs), ctypes.addressof(buf) if per_node else None,
+                                             _stream(stream)), "sgp_pregossip_stats")
         return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
                      cs.argmin, list(buf) if per_node else None)
 

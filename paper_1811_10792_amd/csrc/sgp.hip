@@ -808,16 +808,12 @@ int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *st
     return SGP_OK;
 }
 
-int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
-                        double *per_node_dist_host, void *stream)
+// Launches the stand-alone statistics kernels over z (mode 0) or over the on-the-fly half step
+// (mode 1, 2) and finishes on the host.
+static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
+                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
 {
-    if (!h || !z || !w || !host_out) return SGP_ERR_INVALID_ARG;
-    if (!aligned4(z) || !aligned4(w)) return SGP_ERR_ALIGNMENT;
-    int rc = ensure_device(h);
-    if (rc != SGP_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int n = h->n;
-    const bool vec = (h->ld % 4 == 0) && aligned16(z);
     const long cols4 = vec ? (long)(h->d / 4) : 0;
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);
@@ -826,22 +822,65 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
 
     // every block writes its column of the partial table; blocks beyond the tile count write 0
     bool first = true;
-    auto run = [&](auto vtag, size_t col0, long ncols) {
+    auto run = [&](auto vtag, auto mtag, size_t col0, long ncols) {
         constexpr int V = decltype(vtag)::value;
+        constexpr int MODE = decltype(mtag)::value;
         long ntiles = (ncols + kBlock - 1) / kBlock;
         int acc = first ? 0 : 1;
         if (n <= kStatsCache)
-            hipLaunchKernelGGL(k_stats_small<V>, dim3(G), dim3(kBlock), 0, st, z, n, (size_t)h->ld,
-                               col0, ncols, ntiles, h->d_partial, G, acc);
+            hipLaunchKernelGGL((k_stats_small<V, MODE>), dim3(G), dim3(kBlock), 0, st, z, src, n,
+                               (size_t)h->ld, col0, ncols, ntiles, h->d_partial, G, acc);
         else
-            hipLaunchKernelGGL(k_stats_large<V>, dim3(G), dim3(kBlock), lds_large, st, z, n,
+            hipLaunchKernelGGL((k_stats_large<V, MODE>), dim3(G), dim3(kBlock), lds_large, st, z, src, n,
                                (size_t)h->ld, col0, ncols, ntiles, h->d_partial, G, acc);
         first = false;
     };
-    if (cols4 > 0) run(std::integral_constant<int, 4>{}, 0, cols4);
-    if (tail > 0) run(std::integral_constant<int, 1>{}, tail0, tail);
+    auto both = [&](auto mtag) {
+        if (cols4 > 0) run(std::integral_constant<int, 4>{}, mtag, 0, cols4);
+        if (tail > 0) run(std::integral_constant<int, 1>{}, mtag, tail0, tail);
+    };
+    if (mode == 0) both(std::integral_constant<int, 0>{});
+    else if (mode == 1) both(std::integral_constant<int, 1>{});
+    else both(std::integral_constant<int, 2>{});
     SGP_HIP_TRY(h, hipGetLastError());
     return finish_stats(h, h->d_partial, G, nullptr, w, host_out, per_node_dist_host, st);
+}
+
+int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
+                        double *per_node_dist_host, void *stream)
+{
+    if (!h || !z || !w || !host_out) return SGP_ERR_INVALID_ARG;
+    if (!aligned4(z) || !aligned4(w)) return SGP_ERR_ALIGNMENT;
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    const bool vec = (h->ld % 4 == 0) && aligned16(z);
+    return run_stats(h, z, StatSource{}, 0, vec, w, host_out, per_node_dist_host,
+                     static_cast<hipStream_t>(stream));
+}
+
+int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const float *m, const float *g,
+                        float gamma, float momentum, sgp_stats *host_out, double *per_node_dist_host,
+                        void *stream)
+{
+    if (!h || !x || !w || !g || !host_out) return SGP_ERR_INVALID_ARG;
+    const bool nest = momentum != 0.0f;
+    if (nest && !m) return SGP_ERR_INVALID_ARG;
+    if (!aligned4(x) || !aligned4(w) || !aligned4(g) || (nest && !aligned4(m))) return SGP_ERR_ALIGNMENT;
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    StatSource src{};
+    src.x = x;
+    src.u = m;
+    src.g = g;
+    src.w = h->biased ? nullptr : w;
+    src.hp.gamma = gamma;
+    src.hp.mom = momentum;
+    src.hp.wd = h->wd;
+    src.hp.wd_mode = h->wd == 0.0f ? 0 : (h->wd_on_x || h->biased) ? 1 : 2;
+    src.hp.w_old = w;   // the weights handed in are the ones the coming update will replace
+    const bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m));
+    return run_stats(h, nullptr, src, nest ? 2 : 1, vec, w, host_out, per_node_dist_host,
+                     static_cast<hipStream_t>(stream));
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
