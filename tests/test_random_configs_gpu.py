@@ -1,0 +1,120 @@
+"""Differential test over seeded random configurations of everything the library offers (node
+count, shape, stride, peers, tau, topology, optimiser, weight decay, biased form, z on/off, fused
+statistics): each runs a short trajectory that must equal the float32 oracle's bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sgp_oracle as O
+import paper_1811_10792_amd as sgp
+from paper_1811_10792_amd import binding
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+PAD = -1.125
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def draw(seed):
+    r = np.random.default_rng(seed)
+    c = {}
+    c["n"] = int(r.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 24, 32, 33, 40]))
+    c["d"] = int(r.choice([1, 3, 4, 64, 255, 256, 257, 1000, 2052, 3001]))
+    c["ld"] = c["d"] + int(r.choice([0, 0, 1, 3, 4, 252]))
+    c["topology"] = int(r.choice([0, 0, 0, 1, 2]))
+    c["tau"] = int(r.choice([0, 0, 1, 1, 2, 3])) if c["topology"] == 0 else 0
+    c["peers"] = int(r.choice([1, 1, 2, 2, 3, 4]))
+    c["opt"] = str(r.choice(["sgd", "nesterov", "nesterov", "adam"]))
+    c["wd"] = float(r.choice([0.0, 0.0, 0.02]))
+    c["wd_on_x"] = bool(r.integers(2))
+    c["biased"] = bool(r.integers(4) == 0)
+    c["zout"] = bool(r.integers(5) != 0)
+    c["stats"] = bool(r.integers(3) == 0) and c["opt"] != "adam" and c["zout"]
+    c["w_spread"] = bool(r.integers(2))
+    c["k0"] = int(r.choice([0, 0, 1, 5, 10 ** 6]))
+    return c, r
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_random_configuration(seed):
+    c, rng = draw(seed)
+    n, d, ld, tau = c["n"], c["d"], c["ld"], c["tau"]
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    m1 = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+    m2 = (0.01 * rng.random((n, d))).astype(np.float32)
+    w = (0.5 + rng.random(n)).astype(np.float32) if c["w_spread"] else np.ones(n, np.float32)
+    adam, nest = c["opt"] == "adam", c["opt"] == "nesterov"
+    mom = 0.9 if nest else 0.0
+
+    def pad(a):
+        out = np.full((n, ld), PAD, np.float32)
+        out[:, :d] = a
+        return dev(out)
+    X, M1, M2, G, Z, W = pad(x), pad(m1), pad(m2), pad(np.zeros_like(x)), pad(np.zeros_like(x)), dev(w)
+    eng = sgp.SGP(n, d, ld, topology=c["topology"], peers=c["peers"], delay=tau)
+    if c["wd"]:
+        eng.set_weight_decay(c["wd"], on_numerator=c["wd_on_x"])
+    if c["biased"]:
+        eng.set_biased(True)
+    st = O.OsgpState(n, d, np.float32, tau) if tau else None
+    on_x = c["wd_on_x"] or c["biased"]
+    for it in range(5):
+        k = c["k0"] + it
+        g = (0.3 * rng.standard_normal((n, d))).astype(np.float32)
+        G[:, :d] = dev(g)
+        if c["topology"] == binding.SGP_TOPO_COMPLETE:
+            P = np.full((n, n), np.float32(1.0) / np.float32(n), dtype=np.float32)
+        elif c["topology"] == binding.SGP_TOPO_CUSTOM:
+            M = rng.random((n, n)) * (rng.random((n, n)) < 0.4)
+            M[np.arange(n), np.arange(n)] = rng.random(n) + 0.1
+            P = np.ascontiguousarray((M / M.sum(0, keepdims=True)).astype(np.float32))
+            entries = max(1, int((P != 0).sum(1).max()))
+            idx = [[-1] * entries for _ in range(n)]
+            wts = [[0.0] * entries for _ in range(n)]
+            for i in range(n):
+                for q, j in enumerate(np.nonzero(P[i])[0]):
+                    idx[i][q], wts[i][q] = int(j), float(P[i, j])
+            eng.set_mixing(idx, wts)
+        else:
+            P = O.mixing_matrix(n, c["peers"], k // max(1, tau), np.float32)
+        zt = Z if c["zout"] else None
+        if adam:
+            eng.step_adam(X, W, M1, M2, G, zt, 0.02, 0.9, 0.98, 1e-8, it + 1, k)
+        elif c["stats"]:
+            s = eng.step_stats(X, W, M1 if nest else None, G, Z, 0.05, mom, k, per_node=True)
+        else:
+            eng.step(X, W, M1 if nest else None, G, zt, 0.05, mom, k)
+        kw = dict(nesterov=nest, wd=c["wd"], wd_on_x=on_x)
+        if adam:
+            kw.update(adam=O.adam_params(0.9, 0.98, 1e-8, it + 1, np.float32), v=m2)
+        u_arg = m1 if (nest or adam) else None
+        gam = 0.02 if adam else 0.05
+        if tau:
+            zo = O.step_osgp(P, x, w, u_arg, g, gam, mom, st, k, biased=c["biased"], **kw)
+        else:
+            zo = O.step(P, x, w, u_arg, g, gam, mom, **kw)
+            if c["biased"]:
+                zo = x.copy()
+        tag = "%s k=%d" % (c, k)
+        assert np.array_equal(host(W), w), "w " + tag
+        assert np.array_equal(host(X)[:, :d], x), "x " + tag
+        if c["zout"]:
+            assert np.array_equal(host(Z)[:, :d], zo), "z " + tag
+        if nest or adam:
+            assert np.array_equal(host(M1)[:, :d], m1), "m1 " + tag
+        if adam:
+            assert np.array_equal(host(M2)[:, :d], m2), "m2 " + tag
+        if c["stats"] and n > 1:
+            dist, ref = O.consensus_stats(zo, w)
+            if ref["max"] > 0:
+                assert np.abs(np.array(s.per_node) - dist).max() <= 1e-5 * ref["max"], tag
+    for T in (X, M1, M2, G, Z):
+        assert (host(T)[:, d:] == PAD).all()
+    eng.close()
