@@ -386,8 +386,10 @@ int sgp_destroy(sgp_handle *h)
     if (h->dev_ready) {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) rc = SGP_ERR_HIP;
-        release_device(h);
     }
+    // also after a set-up that failed half way, or mixing rows set on a handle that never stepped:
+    // every pointer is checked on its own
+    release_device(h);
     delete h;
     return rc;
 }

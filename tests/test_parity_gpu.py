@@ -299,8 +299,9 @@ def test_placement_probe_finds_regions_and_separates_the_written_streams():
     assert info["mode"] == "regions"
     t = {r: alloc.floats(r, 4, 1 << 20) for r in ("x", "u", "z", "g")}
     info = alloc.describe()
-    if info["structured"]:                       # three written streams in three different regions
-        assert len({info["arrays"][r] for r in ("x", "u", "z")}) == 3
+    classes = len(set(info["region_of_granule"]))
+    if info["structured"]:                       # the written streams go to different regions
+        assert len({info["arrays"][r] for r in ("x", "u", "z")}) == min(3, classes)
     ptrs = sorted((v.data_ptr(), v.numel() * 4) for v in t.values())
     assert all(a + n <= b for (a, n), (b, _) in zip(ptrs, ptrs[1:]))     # disjoint
     assert all(p % 4096 == 0 for p, _ in ptrs)
