@@ -141,10 +141,20 @@ class Placer:
     def __init__(self, arena: Arena, regions: RegionMap):
         self.arena, self.regions = arena, regions
         ncls = max(regions.classes) + 1
-        # free runs per class as [start_byte, end_byte)
-        self.free: Dict[int, List[List[int]]] = {
-            c: [[s * regions.granule, (s + k) * regions.granule] for s, k in regions.runs(c)]
-            for c in range(ncls)}
+        # free ranges per class as [start_byte, end_byte), in the order they are tried: the interiors
+        # of the long runs first, longest first (a granule at the edge of a run may straddle a region
+        # boundary, and a short run may be a timing outlier), then what was trimmed off, then short runs
+        g = regions.granule
+        self.free: Dict[int, List[List[int]]] = {}
+        for c in range(ncls):
+            inner, edges, short = [], [], []
+            for s0, k in sorted(regions.runs(c), key=lambda r: -r[1]):
+                if k >= 4:
+                    inner.append([(s0 + 1) * g, (s0 + k - 1) * g])
+                    edges += [[s0 * g, (s0 + 1) * g], [(s0 + k - 1) * g, (s0 + k) * g]]
+                else:
+                    short.append([s0 * g, (s0 + k) * g])
+            self.free[c] = inner + edges + short
         # classes ordered by capacity, largest first
         self.order = sorted(range(ncls), key=lambda c: -regions.capacity(c))
 
