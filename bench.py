@@ -3,8 +3,10 @@
 
 A "step" is one pass of the whole hot path over all n simulated nodes: peer schedule, momentum
 update, local step, PushSum mix of x and w, de-bias and (for the workloads that ask for it) the
-consensus statistics, i.e. one sgp_step_stats call (statistics accumulated inside the step kernel;
---separate-stats: one sgp_step call plus one sgp_consensus_stats call).  All state and a
+consensus statistics: statistics accumulated inside the step kernel, reduced and copied to the
+host in every step, and picked up by the host one step late so that the stream never drains
+(sgp_step_stats_begin / _end; --sync-stats: picked up before the next step is launched,
+sgp_step_stats; --separate-stats: one sgp_step call plus one sgp_consensus_stats call).  All state and a
 small rotating pool of pre-drawn gradient buffers are resident in HBM before the timed region;
 drawing gradients is not part of the step (g is an input of the method).
 
@@ -107,6 +109,9 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    ap.add_argument("--sync-stats", action="store_true",
+                    help="fetch the statistics of every step before launching the next one (sgp_step_stats) "
+                         "instead of one step late (sgp_step_stats_begin / _end)")
     ap.add_argument("--separate-stats", action="store_true",
                     help="run sgp_step and sgp_consensus_stats as two calls instead of sgp_step_stats")
     ap.add_argument("--placement", choices=("regions", "default"), default="regions",
@@ -150,7 +155,12 @@ def main():
     k = 0
     last = None
 
+    pipelined = do_stats and not args.separate_stats and not args.sync_stats and wl.optimizer != "adam"
+
     def one_step(k):
+        if pipelined:       # enqueue step k, then pick up the statistics of step k-1
+            eng.step_stats_begin(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
+            return eng.step_stats_end() if k > 0 else None
         if adam:
             eng.step_adam(X, W, U, V2, pool[k % len(pool)], Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
             return eng.consensus_stats(Z, W) if do_stats else None
@@ -176,6 +186,8 @@ def main():
         k += 1
         if i % 32 == 31:
             kern_ms += eng.step_kernel_times()
+    if pipelined:
+        last = eng.step_stats_end()       # the last step's statistics, inside the timed region
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     kern_ms += eng.step_kernel_times()
@@ -201,7 +213,9 @@ def main():
         "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "topology": wl.topology,
                    "peers": wl.peers, "delay": wl.delay,
                    "optimizer": wl.optimizer, "momentum": wl.momentum, "gamma": wl.gamma,
-                   "consensus_stats_each_step": bool(do_stats), "gradient_pool": len(pool),
+                   "consensus_stats_each_step": bool(do_stats),
+                   "stats_fetch": ("one step late" if pipelined else "every step") if do_stats else None,
+                   "gradient_pool": len(pool),
                    "placement": alloc.describe()},
         "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

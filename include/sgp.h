@@ -233,6 +233,19 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
                    double *per_node_dist_host, void *stream);
 
 /*
+ * The same work as sgp_step_stats without draining the stream every iteration.
+ * sgp_step_stats_begin enqueues iteration k, the statistics of the z it writes and their copy to
+ * the host, and returns at once; sgp_step_stats_end hands out the oldest result not yet fetched,
+ * waiting (for that result only) if it is not there yet.  At most two results may be outstanding:
+ * a third begin returns SGP_ERR_SEQUENCE, as does an end with nothing outstanding.  Typical loop:
+ * begin(k); if (k > 0) end(result of k-1); ... ; end(last).  The GPU then never waits for the host.
+ * All begin calls between two ends must use streams that are ordered with respect to each other.
+ */
+int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+                         float gamma, float momentum, int64_t k, void *stream);
+int sgp_step_stats_end(sgp_handle *h, sgp_stats *host_out, double *per_node_dist_host);
+
+/*
  * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).  Exponential graph only
  * (SGP_ERR_UNSUPPORTED otherwise).
  *   out_peers [n][peers] : out_peers[i*peers + r] = node that i sends to over its r-th hop,

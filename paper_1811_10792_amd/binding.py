@@ -31,7 +31,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
-           "sgp_pregossip_stats")
+           "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end")
 
 
 class SgpError(RuntimeError):
@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_set_weight_decay.argtypes = [vp, f32, ctypes.c_int]
     lib.sgp_set_topology.argtypes = [vp, i32, i32]
     lib.sgp_set_mixing.argtypes = [vp, vp, vp, i32]
+    lib.sgp_step_stats_begin.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, vp]
+    lib.sgp_step_stats_end.argtypes = [vp, ctypes.POINTER(_CStats), vp]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -203,6 +205,23 @@ class SGP:
                                         gamma, momentum, k, ctypes.byref(cs),
                                         ctypes.addressof(buf) if per_node else None,
                                         _stream(stream)), "sgp_step_stats")
+        return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
+                     cs.argmin, list(buf) if per_node else None)
+
+    def step_stats_begin(self, x, w, m, g, z_out, gamma: float, momentum: float, k: int, stream=None) -> None:
+        """Enqueues iteration k and the statistics of its z; fetch them later with step_stats_end()."""
+        for t, name in ((x, "x"), (m, "m"), (g, "g"), (z_out, "z_out")):
+            self._expect(t, name)
+        self._expect(w, "w", rows_only=True)
+        _check(self._lib.sgp_step_stats_begin(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g), _ptr(z_out),
+                                              gamma, momentum, k, _stream(stream)), "sgp_step_stats_begin")
+
+    def step_stats_end(self, per_node: bool = False) -> Stats:
+        """The oldest result of step_stats_begin not yet fetched (waits for it if necessary)."""
+        cs = _CStats()
+        buf = (ctypes.c_double * self.n)() if per_node else None
+        _check(self._lib.sgp_step_stats_end(self._h, ctypes.byref(cs),
+                                            ctypes.addressof(buf) if per_node else None), "sgp_step_stats_end")
         return Stats(cs.dist_max, cs.dist_mean, cs.dist_min, cs.w_sum, cs.zbar_norm, cs.argmax,
                      cs.argmin, list(buf) if per_node else None)
 

@@ -108,8 +108,11 @@ struct sgp_handle {
     int G;
     double *d_sums;     // [n+1] per-node sums of squares (+ the average's), or the fused kernel's
                         // [kSlotSumBlocks][33] block sums
-    double *d_result;   // [8 + n]
+    double *d_result;   // [kResultSlots][8 + n]: slot 0 for the synchronous calls, 1.. for begin/end
     double *h_result;   // pinned mirror
+    hipEvent_t ev_res[2];   // results of sgp_step_stats_begin copied to the host
+    bool ev_res_made;
+    int pend_head, pend_count;   // ring of outstanding begin/end results (slots 1 + index)
     float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
     bool msg_external;  // d_msg points into caller-owned memory
     float *d_msgw[2];   // overlap mode: pre-weighted weights p*w_j, [n] each
@@ -128,6 +131,7 @@ struct sgp_handle {
 namespace {
 
 constexpr int kStatsGridMax = 2048;
+constexpr int kResultSlots = 3;   // statistics results: one synchronous, two in flight
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
@@ -199,9 +203,9 @@ int ensure_device(sgp_handle *h)
     if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
     if (e == hipSuccess) e = hipMalloc(&h->d_sums,
                                        (size_t)std::max(n + 1, kSlotSumBlocks * (kStatsCache + 1)) * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)(8 + n) * sizeof(double));
+    if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)kResultSlots * (8 + n) * sizeof(double));
     if (e == hipSuccess)
-        e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)(8 + n) * sizeof(double),
+        e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)kResultSlots * (8 + n) * sizeof(double),
                           hipHostMallocDefault);
     if (e == hipSuccess && h->delay) {
         size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
@@ -222,6 +226,10 @@ void release_device(sgp_handle *h)
             (void)hipEventDestroy(h->ev[i][0]);
             (void)hipEventDestroy(h->ev[i][1]);
         }
+    if (h->ev_res_made) {
+        (void)hipEventDestroy(h->ev_res[0]);
+        (void)hipEventDestroy(h->ev_res[1]);
+    }
     if (h->d_tab) (void)hipFree(h->d_tab);
     if (h->d_cidx) (void)hipFree(h->d_cidx);
     if (h->d_cw) (void)hipFree(h->d_cw);
@@ -721,34 +729,52 @@ int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const
     return step_impl(h, x, w, m1, g, z_out, gamma, 0.0f, k, stream, nullptr, &adam);
 }
 
-// Reduces a partial table to the statistics, copies them to the host and waits.  fused == NULL:
-// the stand-alone kernels' table [(n+1)][G]; else the fused kernel's.
-static int finish_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
-                        sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
+// Enqueues the reduction of a partial table to the statistics and their copy into result slot
+// `slot` of the pinned host buffer.  fused == NULL: the stand-alone kernels' table [(n+1)][G];
+// else the fused kernel's.
+static int enqueue_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
+                         int slot, hipStream_t st)
 {
     const int n = h->n;
+    double *d_res = h->d_result + (size_t)slot * (8 + n);
     if (fused) {
         const int B = std::min(kSlotSumBlocks, G);
         hipLaunchKernelGGL(k_stats_slotsum, dim3(B), dim3(kSlotSumBlock), 0, st, partial, G, h->d_sums);
         hipLaunchKernelGGL(k_stats_final_slots, dim3(1), dim3(kFinalSlotsBlock), 0, st, h->d_sums, B, n, fused->hop,
-                           fused->len, w, h->d_result);
+                           fused->len, w, d_res);
     } else {
         hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);
-        hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, h->d_result);
+        hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, d_res);
     }
     SGP_HIP_TRY(h, hipGetLastError());
-    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result, h->d_result, (size_t)(8 + n) * sizeof(double),
+    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result + (size_t)slot * (8 + n), d_res, (size_t)(8 + n) * sizeof(double),
                                   hipMemcpyDeviceToHost, st));
-    SGP_HIP_TRY(h, hipStreamSynchronize(st));
-    host_out->dist_max = h->h_result[0];
-    host_out->dist_mean = h->h_result[1];
-    host_out->dist_min = h->h_result[2];
-    host_out->w_sum = h->h_result[3];
-    host_out->zbar_norm = h->h_result[4];
-    host_out->argmax = (int32_t)h->h_result[5];
-    host_out->argmin = (int32_t)h->h_result[6];
+    return SGP_OK;
+}
+
+static void read_stats(const sgp_handle *h, int slot, sgp_stats *host_out, double *per_node_dist_host)
+{
+    const int n = h->n;
+    const double *r = h->h_result + (size_t)slot * (8 + n);
+    host_out->dist_max = r[0];
+    host_out->dist_mean = r[1];
+    host_out->dist_min = r[2];
+    host_out->w_sum = r[3];
+    host_out->zbar_norm = r[4];
+    host_out->argmax = (int32_t)r[5];
+    host_out->argmin = (int32_t)r[6];
     if (per_node_dist_host)
-        for (int i = 0; i < n; ++i) per_node_dist_host[i] = h->h_result[8 + i];
+        for (int i = 0; i < n; ++i) per_node_dist_host[i] = r[8 + i];
+}
+
+// Reduces a partial table to the statistics, copies them to the host and waits.
+static int finish_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
+                        sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
+{
+    int rc = enqueue_stats(h, partial, G, fused, w, 0, st);
+    if (rc != SGP_OK) return rc;
+    SGP_HIP_TRY(h, hipStreamSynchronize(st));
+    read_stats(h, 0, host_out, per_node_dist_host);
     return SGP_OK;
 }
 
@@ -764,6 +790,48 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
         return finish_stats(h, h->d_partial_f, fused.G, &fused, w, host_out, per_node_dist_host,
                             static_cast<hipStream_t>(stream));
     return sgp_consensus_stats(h, z_out, w, host_out, per_node_dist_host, stream);
+}
+
+static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
+                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot);
+
+int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
+                         float gamma, float momentum, int64_t k, void *stream)
+{
+    if (!h || !z_out) return SGP_ERR_INVALID_ARG;
+    if (h->pend_count >= 2) return SGP_ERR_SEQUENCE;   // fetch a result with sgp_step_stats_end first
+    FusedStats fused;
+    int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
+    if (rc != SGP_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!h->ev_res_made) {
+        SGP_HIP_TRY(h, hipEventCreateWithFlags(&h->ev_res[0], hipEventDisableTiming));
+        SGP_HIP_TRY(h, hipEventCreateWithFlags(&h->ev_res[1], hipEventDisableTiming));
+        h->ev_res_made = true;
+    }
+    const int idx = (h->pend_head + h->pend_count) % 2;
+    if (fused.G > 0) {
+        rc = enqueue_stats(h, h->d_partial_f, fused.G, &fused, w, 1 + idx, st);
+    } else {
+        const bool vec = (h->ld % 4 == 0) && aligned16(z_out);
+        rc = run_stats(h, z_out, StatSource{}, 0, vec, w, nullptr, nullptr, st, 1 + idx);
+    }
+    if (rc != SGP_OK) return rc;
+    SGP_HIP_TRY(h, hipEventRecord(h->ev_res[idx], st));
+    ++h->pend_count;
+    return SGP_OK;
+}
+
+int sgp_step_stats_end(sgp_handle *h, sgp_stats *host_out, double *per_node_dist_host)
+{
+    if (!h || !host_out) return SGP_ERR_INVALID_ARG;
+    if (h->pend_count == 0) return SGP_ERR_SEQUENCE;
+    const int idx = h->pend_head;
+    SGP_HIP_TRY(h, hipEventSynchronize(h->ev_res[idx]));
+    read_stats(h, 1 + idx, host_out, per_node_dist_host);
+    h->pend_head = (idx + 1) % 2;
+    --h->pend_count;
+    return SGP_OK;
 }
 
 int sgp_set_kernel_timing(sgp_handle *h, int enable)
@@ -813,7 +881,7 @@ int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *st
 // Launches the stand-alone statistics kernels over z (mode 0) or over the on-the-fly half step
 // (mode 1, 2) and finishes on the host.
 static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
-                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
+                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot)
 {
     const int n = h->n;
     const long cols4 = vec ? (long)(h->d / 4) : 0;
@@ -845,6 +913,7 @@ static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int m
     else if (mode == 1) both(std::integral_constant<int, 1>{});
     else both(std::integral_constant<int, 2>{});
     SGP_HIP_TRY(h, hipGetLastError());
+    if (slot != 0) return enqueue_stats(h, h->d_partial, G, nullptr, w, slot, st);
     return finish_stats(h, h->d_partial, G, nullptr, w, host_out, per_node_dist_host, st);
 }
 
@@ -857,7 +926,7 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
     if (rc != SGP_OK) return rc;
     const bool vec = (h->ld % 4 == 0) && aligned16(z);
     return run_stats(h, z, StatSource{}, 0, vec, w, host_out, per_node_dist_host,
-                     static_cast<hipStream_t>(stream));
+                     static_cast<hipStream_t>(stream), 0);
 }
 
 int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const float *m, const float *g,
@@ -882,7 +951,7 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
     src.hp.w_old = w;   // the weights handed in are the ones the coming update will replace
     const bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m));
     return run_stats(h, nullptr, src, nest ? 2 : 1, vec, w, host_out, per_node_dist_host,
-                     static_cast<hipStream_t>(stream));
+                     static_cast<hipStream_t>(stream), 0);
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
