@@ -34,7 +34,7 @@ def _parse_four_node(golden_dir):
 
 
 def _facts(golden_dir):
-    out = {"NEIGHBOUR": [], "COLUMN": [], "TWOPEER": [], "EXACT": []}
+    out = {"NEIGHBOUR": [], "COLUMN": [], "TWOPEER": [], "EXACT": [], "CONTRACTION": []}
     with open(os.path.join(golden_dir, "exponential_graph_facts.txt")) as f:
         for line in f:
             t = line.split()
@@ -237,6 +237,52 @@ def test_brute_force_dense_product():
                 assert np.abs(x - want_x).max() < 1e-14
                 assert np.abs(w - want_w).max() < 1e-15
                 assert np.abs(z - want_x / want_w[:, None]).max() < 1e-13
+
+
+def _one_peer_matrix(n, dest):
+    """Column-stochastic one-peer matrix: node i keeps half and sends half to dest[i]."""
+    P = np.zeros((n, n))
+    for i in range(n):
+        P[i, i] += 0.5
+        P[dest[i], i] += 0.5
+    return P
+
+
+def test_printed_contraction_factors_of_other_one_peer_schemes(golden_dir):
+    # "Decentralized averaging errors": sigma_2^2 of the product of five mixing matrices is the number
+    # the paper prints for each scheme (to its one printed digit); the oracle's mix applies exactly
+    # that product and, for the doubly stochastic scheme, contracts the worst-case start by it
+    rng = np.random.default_rng(2024)
+    for scheme, n, its, printed in _facts(golden_dir)["CONTRACTION"]:
+        n, its, printed = int(n), int(its), float(printed)
+        trials = 1 if scheme == "complete_cycle" else 200
+        factors = []
+        for _ in range(trials):
+            Ps = []
+            for k in range(its):
+                if scheme == "complete_cycle":
+                    dest = [(i + k + 1) % n for i in range(n)]
+                elif scheme == "random_exponential":
+                    dest = [(i + 2 ** int(rng.integers(5))) % n for i in range(n)]
+                else:
+                    dest = [(i + 1 + int(rng.integers(n - 1))) % n for i in range(n)]
+                Ps.append(_one_peer_matrix(n, dest))
+            prod = np.eye(n)
+            for P in Ps:
+                prod = P @ prod
+            _, sv, vt = np.linalg.svd(prod)
+            y0 = np.ascontiguousarray(vt[1][:, None] * np.ones((1, 3)))   # worst-case start, 3 coordinates
+            y, w = y0.copy(), np.ones(n)
+            for P in Ps:
+                O.step(np.ascontiguousarray(P), y, w, None, np.zeros_like(y), 0.0, 0.0, nesterov=False)
+            assert np.abs(y - prod @ y0).max() < 1e-14            # the oracle applies exactly this product
+            if scheme == "complete_cycle":
+                # doubly stochastic: the average is kept and the worst-case start contracts by sigma_2^2
+                e0 = ((y0 - y0.mean(0)) ** 2).sum()
+                assert abs(((y - y.mean(0)) ** 2).sum() / e0 - sv[1] ** 2) < 1e-12
+                assert np.abs(y.mean(0) - y0.mean(0)).max() < 1e-15 and np.abs(w - 1).max() < 1e-15
+            factors.append(sv[1] ** 2)
+        assert abs(np.mean(factors) - printed) < 0.05, (scheme, np.mean(factors))
 
 
 # ------------------------------------------------- reductions to textbook / library routines

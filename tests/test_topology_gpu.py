@@ -179,3 +179,38 @@ def test_topology_error_paths():
         eng.set_topology(binding.SGP_TOPO_COMPLETE, 1)
     assert e.value.status == binding.SGP_ERR_UNSUPPORTED
     eng.close()
+
+
+def test_averaging_error_of_complete_graph_cycling_matches_printed_factor():
+    """"Decentralized averaging errors": one-peer cycling through the edges of the complete graph
+    (hop k+1 at iteration k), n = 32: after 5 iterations the squared consensus error of the worst-case
+    start has shrunk by about 0.6, while the exponential graph has reached the exact average."""
+    n, d = 32, 4096
+    Ps = []
+    for k in range(5):
+        P = np.zeros((n, n), np.float32)
+        for i in range(n):
+            P[i, i] = 0.5
+            P[(i + k + 1) % n, i] = 0.5
+        Ps.append(P)
+    prod = np.eye(n)
+    for P in Ps:
+        prod = P.astype(np.float64) @ prod
+    _, sv, vt = np.linalg.svd(prod)
+    y0 = (vt[1][:, None] * np.linspace(0.5, 1.5, d)[None, :]).astype(np.float32)
+    for scheme in ("complete_cycle", "exponential"):
+        eng = sgp.SGP(n, d, topology=binding.SGP_TOPO_CUSTOM if scheme == "complete_cycle" else 0)
+        X, W = dev(y0), dev(np.ones(n, np.float32))
+        G, Z = torch.zeros_like(X), torch.zeros_like(X)
+        eng.debias(X, W, Z)
+        e0 = sum(v * v for v in eng.consensus_stats(Z, W, per_node=True).per_node)
+        for k in range(5):
+            if scheme == "complete_cycle":
+                eng.set_mixing(*sparse_rows(Ps[k]))
+            s = eng.step_stats(X, W, None, G, Z, 0.0, 0.0, k, per_node=True)
+        e5 = sum(v * v for v in s.per_node)
+        if scheme == "complete_cycle":
+            assert abs(e5 / e0 - sv[1] ** 2) < 1e-4 and abs(e5 / e0 - 0.6) < 0.05
+        else:
+            assert e5 == 0.0
+        eng.close()
