@@ -114,6 +114,10 @@ def main():
                          "instead of one step late (sgp_step_stats_begin / _end)")
     ap.add_argument("--separate-stats", action="store_true",
                     help="run sgp_step and sgp_consensus_stats as two calls instead of sgp_step_stats")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one cycle of the peer schedule (L iterations) into a HIP graph and time "
+                         "replays of it: for small models, where launch overhead dominates (blocking mode "
+                         "without statistics only; the step kernels are not timed individually)")
     ap.add_argument("--placement", choices=("regions", "default"), default="regions",
                     help="regions: carve the state arrays out of one arena so that the written "
                          "streams x, u, z sit in different HBM regions (found by timing); "
@@ -169,6 +173,40 @@ def main():
                                   wl.momentum, k)
         eng.step(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
         return eng.consensus_stats(Z, W) if do_stats else None
+
+    if args.graph:
+        if do_stats or wl.delay or adam:
+            sys.exit("bench.py --graph: blocking workloads without statistics only")
+        L = max(1, (n - 1).bit_length())
+        one_step(0)                                   # sets up the library's device tables
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for kk in range(L):
+                one_step(kk)
+        reps = max(1, args.steps // L)
+        for _ in range(max(1, args.warmup // L)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        steps = reps * L
+        print(json.dumps({
+            "metric": "SGP node-param updates/sec (n*d/step time) + achieved HBM GB/s vs peak",
+            "value": n * d * steps / elapsed, "unit": "node-param updates/s", "n_gpus": 1, "steps": steps,
+            "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "launch": "HIP graph of %d iterations" % L},
+            "roofline": {"bound": "hbm", "kernel": "whole graph",
+                         "achieved": algorithmic_bytes_per_update(wl) * n * d * steps / elapsed / 1e9,
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": algorithmic_bytes_per_update(wl) * n * d * steps / elapsed / 1e9 / HBM_PEAK_GBPS,
+                         "traffic": None}}), flush=True)
+        eng.close()
+        return
 
     for _ in range(args.warmup):
         last = one_step(k)
