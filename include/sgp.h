@@ -49,7 +49,7 @@ extern "C" {
 
 #define SGP_TOPO_DIRECTED_EXP 0 /* time-varying directed exponential graph (Appendix A) */
 #define SGP_TOPO_COMPLETE 1     /* every entry of P equal to 1/n: SGP then coincides with parallel
-                                   SGD over AllReduce (section 3, "every entry ... equal to 1/n") */
+                                   SGD over AllReduce (section 3) */
 #define SGP_TOPO_CUSTOM 2       /* caller-supplied sparse rows of P, see sgp_set_mixing */
 
 #define SGP_MAX_NODES 1024 /* largest n accepted by sgp_create */
@@ -133,7 +133,7 @@ int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight,
 /*
  * Weight decay fused into the local step (the hyperparameter appendix: the ImageNet runs use
  * weight decay 1e-4 with Nesterov momentum): from the next sgp_step on, g_i is replaced by
- * g_i + weight_decay * theta_i before Alg. 1 line 4 / Alg. 3 lines 4-5, where theta_i is the
+ * g_i + weight_decay * theta_i before the local step of Alg. 1 / Alg. 3, where theta_i is the
  * de-biased z_i^(k) = x_i^(k) / w_i^(k) (on_numerator == 0; the gradient of the L2 term at the
  * point where g_i was evaluated) or the numerator x_i^(k) (on_numerator != 0; what an optimizer
  * that steps on the biased parameters applies).  The paper does not say which; they coincide
@@ -153,7 +153,7 @@ int sgp_set_biased(sgp_handle *h, int biased);
 int sgp_reset(sgp_handle *h);
 
 /*
- * One SGP iteration k for all nodes (Alg. 1 lines 4-8 / Alg. 3 lines 4-9; overlap mode: Alg. 2
+ * One SGP iteration k for all nodes (the loop body of Alg. 1 / Alg. 3; overlap mode: Alg. 2
  * with tau = 1), in place.
  *   x        [n][ld] device, in/out : push-sum numerators x^(k) -> x^(k+1)
  *   w        [n]     device, in/out : push-sum weights   w^(k) -> w^(k+1)
@@ -209,9 +209,9 @@ int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats
 
 /*
  * The same statistics at the measurement point of the figure on parameter deviations: after the
- * local step and before communication ("just after line 4 in Alg. 1").  Takes the state BEFORE
- * iteration k and the gradient of iteration k, forms xh_i as sgp_step would (Alg. 1 line 4, or
- * Alg. 3 lines 4-5 when momentum != 0, weight decay included) and reports the deviations of
+ * local step and before communication (the gradient step of Alg. 1 done, nothing sent yet).  Takes the state BEFORE
+ * iteration k and the gradient of iteration k, forms xh_i as sgp_step would (gradient step of Alg. 1, or
+ * momentum and gradient steps of Alg. 3 when momentum != 0, weight decay included) and reports the deviations of
  * xh_i / w_i from their node-wise average.  Nothing is modified: call it before the sgp_step that
  * consumes the same g.  Reads x, g (and m) once (twice for n > 32).  SYNCHRONISES the stream.
  */

@@ -4,7 +4,7 @@
 // Kernel design.  The PushSum mix couples nodes but never coordinates (x <- P x acts on the
 // n-vector of one coordinate), so a work-item owns a 128-bit group of four coordinates for ALL
 // n nodes.  It reads x, u, g of every node once, writes u, x, z once, and the "messages" of
-// Alg. 1 line 5 never leave registers (or LDS): 24 bytes of HBM traffic per node-parameter, the
+// Alg. 1's send/receive step never leave registers (or LDS): 24 bytes of HBM traffic per node-parameter, the
 // algorithmic minimum, and the in-place update is race-free because no other work-item touches
 // those coordinates.  Everything is a stream (about 0.4 flop per byte), so there is no MFMA
 // here; what matters is 128-bit coalesced accesses and enough loads in flight per CU.
