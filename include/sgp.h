@@ -20,7 +20,12 @@
  * otherwise a scalar path is used.  For full bandwidth choose ld as a multiple of 256 elements so
  * that every row starts on a 1 KiB boundary: rows that start off a 128-byte boundary split each
  * wavefront's 1 KiB access over an extra cache line and cost about 15 % of the achieved HBM
- * bandwidth (measured on MI355X).  Arithmetic is IEEE binary32, round to nearest even, every
+ * bandwidth (measured on MI355X).  Where the arrays sit matters as well: the 288 GiB of HBM behave as
+ * three 96 GiB regions, and arrays that are written at the same time (x, m, z) slow each other down
+ * when they share one; with x (and g), m and z in three different regions the step kernels reach
+ * 80 % of the HBM peak, with back-to-back allocations 64 %.  The library takes the pointers as they
+ * come; the Python package's placement module finds the regions by timing and carves the arrays.
+ * Arithmetic is IEEE binary32, round to nearest even, every
  * operation rounded separately (no fused multiply-add), correctly rounded division, subnormals
  * kept.  Sums over senders are taken in ascending sender index.
  *
