@@ -135,3 +135,9 @@ def test_biased_flag_can_be_switched_between_steps():
 
 def test_step_stats_falls_back_under_tau_overlap():
     trajectory(8, 4096, 4096, 1, 2, 6, 0.9, seed=77, stats=True)
+
+
+@pytest.mark.parametrize("peers,tau", [(1, 0), (1, 1), (2, 1), (2, 3)])
+def test_largest_node_count(peers, tau):
+    """SGP_MAX_NODES = 1024 nodes (the blocking two-peer gather is limited to 256 and not meant here)."""
+    trajectory(1024, 260, 260, peers, tau, 4, 0.9, seed=1024 + peers + tau, w_spread=True)
