@@ -41,9 +41,6 @@
 #ifndef SGP_OP_BLOCK
 #define SGP_OP_BLOCK 64
 #endif
-#ifndef SGP_OP_DYNLDS
-#define SGP_OP_DYNLDS 0   // unused dynamic LDS per block: an occupancy limiter for experiments
-#endif
 #ifndef SGP_OP_COLS
 #define SGP_OP_COLS 1
 #endif
@@ -263,7 +260,7 @@ template <int V, int OPT, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
     hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
-                       dim3(kOpBlock), SGP_OP_DYNLDS,
+                       dim3(kOpBlock), 0,
                        a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
                        len, a.p, a.hp);
 }
