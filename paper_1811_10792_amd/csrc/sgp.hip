@@ -308,10 +308,12 @@ void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_p
         hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
+#if !SGP_DELAY_WINDOW
     else if (nm == 2)
         hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
+#endif
     else
         hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
                            a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
