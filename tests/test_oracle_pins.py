@@ -285,6 +285,26 @@ def test_printed_contraction_factors_of_other_one_peer_schemes(golden_dir):
         assert abs(np.mean(factors) - printed) < 0.05, (scheme, np.mean(factors))
 
 
+def test_deviation_plateau_is_proportional_to_the_step_size():
+    # "Parameter deviations" / the consensus lemma behind it: nodes converge to a neighbourhood of
+    # the average whose size is proportional to the step size.  Heterogeneous quadratics with
+    # gradient noise: halving gamma halves the stationary mean distance to the node-wise average.
+    def plateau(gamma, n=8, d=64, iters=600):
+        rng = np.random.default_rng(5)
+        h = 0.5 + 1.5 * rng.random((n, d))
+        c = rng.standard_normal((n, d))
+        x = rng.standard_normal((n, d))
+        w, z, acc = np.ones(n), x.copy(), []
+        for k in range(iters):
+            g = h * (z - c) + 0.1 * rng.standard_normal((n, d))
+            z = O.step(O.mixing_matrix(n, 1, k), x, w, None, g, gamma, 0.0, nesterov=False)
+            if k >= iters - 200:
+                acc.append(O.consensus_stats(z, w)[1]["mean"])
+        return float(np.mean(acc))
+    p1, p2, p4 = plateau(0.1), plateau(0.05), plateau(0.025)
+    assert 1.8 < p1 / p2 < 2.2 and 1.8 < p2 / p4 < 2.2
+
+
 # ------------------------------------------------- reductions to textbook / library routines
 @pytest.mark.parametrize("nesterov,m", [(False, 0.0), (True, 0.9), (True, 0.5)])
 def test_all_to_all_equals_parallel_sgd_library(nesterov, m):
