@@ -395,6 +395,10 @@ def test_full_size_config4_n32_resnet50():
     _full_size_spot_check(syn.WORKLOADS["c4_n32_resnet50"], steps=3)
 
 
+def test_full_size_config4_whole_run_of_50_iterations():
+    _full_size_spot_check(syn.WORKLOADS["c4_n32_resnet50"], steps=50, count=600)
+
+
 def test_full_size_config5_n16_transformer_two_peer_overlap():
     _full_size_spot_check(syn.WORKLOADS["c5_n16_transformer_2peer_overlap"], steps=3)
 
