@@ -251,6 +251,27 @@ int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const floa
 int sgp_step_stats_end(sgp_handle *h, sgp_stats *host_out, double *per_node_dist_host);
 
 /*
+ * sgp_consensus_stats for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Handle-free; calls no hipMalloc / hipFree / hipHostMalloc
+ * and does not synchronise.  Its scratch (the [(n+1)][2048] float table of partial sums and n+1
+ * doubles) is a fixed device array inside the library, about 1.06 MB, which every GPU the library
+ * runs on holds until the process ends; n is therefore limited to SGP_NOALLOC_MAX_NODES.
+ *   z [n][ld] device, w [n] device : as for sgp_consensus_stats
+ *   out_device [8 + n] doubles, device, 8-byte aligned, written by the last kernel enqueued:
+ *       out[0] dist_max, [1] dist_mean, [2] dist_min, [3] sum_i w_i, [4] ||zbar||_2, [5] argmax,
+ *       [6] argmin (both as doubles), [7] 0, out[8 + i] = || z_i - zbar ||_2
+ * Runs the same kernels as sgp_consensus_stats, so the values are identical to that call's.
+ * All calls on one GPU share that GPU's scratch array: calls whose kernels overlap in time on one
+ * GPU (different streams, or different host threads) race; order them.  Nothing in the array has to
+ * be cleared between calls (every entry that is read has been written by the same call).
+ * Errors: SGP_ERR_INVALID_ARG (null pointer, n < 1, d < 1, ld < d), SGP_ERR_UNSUPPORTED
+ * (n > SGP_NOALLOC_MAX_NODES), SGP_ERR_ALIGNMENT, SGP_ERR_HIP.
+ */
+#define SGP_NOALLOC_MAX_NODES 128
+int sgp_consensus_stats_noalloc(int32_t n, int64_t d, int64_t ld, const float *z, const float *w,
+                                double *out_device, void *stream);
+
+/*
  * Peer schedule of iteration k (host-only, integer arithmetic; Appendix A).  Exponential graph only
  * (SGP_ERR_UNSUPPORTED otherwise).
  *   out_peers [n][peers] : out_peers[i*peers + r] = node that i sends to over its r-th hop,

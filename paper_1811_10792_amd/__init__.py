@@ -4,6 +4,8 @@ csrc/sgp.hip holds the HIP kernels and the C ABI of include/sgp.h; binding.py ma
 arguments; synthetic.py draws the seeded benchmark inputs.  Importing the package loads nothing;
 the HIP library is loaded on first use and its absence is an error.
 """
-from .binding import SGP, SgpError, Stats, load_library, sgp_copy, sgp_schedule, status_string  # noqa: F401
+from .binding import (SGP, SgpError, Stats, load_library, sgp_consensus_stats_noalloc, sgp_copy,  # noqa: F401
+                      sgp_schedule, status_string)
 
-__all__ = ["SGP", "SgpError", "Stats", "load_library", "sgp_copy", "sgp_schedule", "status_string"]
+__all__ = ["SGP", "SgpError", "Stats", "load_library", "sgp_consensus_stats_noalloc", "sgp_copy", "sgp_schedule",
+           "status_string"]

@@ -31,7 +31,8 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_last_hip_error", "sgp_copy", "sgp_set_kernel_timing", "sgp_step_kernel_times",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
-           "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end")
+           "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
+           "sgp_consensus_stats_noalloc")
 
 
 class SgpError(RuntimeError):
@@ -96,6 +97,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_step_stats_begin.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, vp]
     lib.sgp_step_stats_end.argtypes = [vp, ctypes.POINTER(_CStats), vp]
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
+    lib.sgp_consensus_stats_noalloc.argtypes = [i32, i64, i64, vp, vp, vp, vp]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     for name in EXPORTS:
         if name != "sgp_status_string":
@@ -142,6 +144,13 @@ def sgp_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
     if nbytes is None:
         nbytes = src.numel() * src.element_size()
     _check(load_library().sgp_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sgp_copy")
+
+
+def sgp_consensus_stats_noalloc(n: int, d: int, ld: int, z, w, out_device, stream=None) -> None:
+    """Statistics of z into the device tensor out_device ([8 + n] float64) without any allocation
+    and without synchronising; layout as in include/sgp.h."""
+    _check(load_library().sgp_consensus_stats_noalloc(n, d, ld, _ptr(z), _ptr(w), _ptr(out_device),
+                                                      _stream(stream)), "sgp_consensus_stats_noalloc")
 
 
 class SGP:

@@ -29,6 +29,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "sgp.h"
@@ -878,18 +879,16 @@ int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *st
 }
 
 // Launches the stand-alone statistics kernels over z (mode 0) or over the on-the-fly half step
-// (mode 1, 2) and finishes on the host.
-static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
-                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot)
+// (mode 1, 2): every block writes its column of the partial table [(n+1)][G]; blocks beyond the tile
+// count write 0, so the table needs no clearing.
+static void launch_stats_passes(int n, int64_t d, int64_t ld, const float *z, const StatSource &src, int mode,
+                                bool vec, float *partial, int G, hipStream_t st)
 {
-    const int n = h->n;
-    const long cols4 = vec ? (long)(h->d / 4) : 0;
+    const long cols4 = vec ? (long)(d / 4) : 0;
     const size_t tail0 = (size_t)cols4 * 4;
-    const long tail = (long)(h->d - (int64_t)tail0);
-    const int G = h->G;
+    const long tail = (long)(d - (int64_t)tail0);
     const size_t lds_large = (size_t)(kBlock / 64) * (n + 1) * sizeof(float);
 
-    // every block writes its column of the partial table; blocks beyond the tile count write 0
     bool first = true;
     auto run = [&](auto vtag, auto mtag, size_t col0, long ncols) {
         constexpr int V = decltype(vtag)::value;
@@ -898,10 +897,10 @@ static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int m
         int acc = first ? 0 : 1;
         if (n <= kStatsCache)
             hipLaunchKernelGGL((k_stats_small<V, MODE>), dim3(G), dim3(kBlock), 0, st, z, src, n,
-                               (size_t)h->ld, col0, ncols, ntiles, h->d_partial, G, acc);
+                               (size_t)ld, col0, ncols, ntiles, partial, G, acc);
         else
             hipLaunchKernelGGL((k_stats_large<V, MODE>), dim3(G), dim3(kBlock), lds_large, st, z, src, n,
-                               (size_t)h->ld, col0, ncols, ntiles, h->d_partial, G, acc);
+                               (size_t)ld, col0, ncols, ntiles, partial, G, acc);
         first = false;
     };
     auto both = [&](auto mtag) {
@@ -911,9 +910,17 @@ static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int m
     if (mode == 0) both(std::integral_constant<int, 0>{});
     else if (mode == 1) both(std::integral_constant<int, 1>{});
     else both(std::integral_constant<int, 2>{});
+}
+
+// The stand-alone statistics on a handle: the passes above, then the final reduction, into result
+// slot `slot` (0: copy to the host and wait; else enqueue only).
+static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
+                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot)
+{
+    launch_stats_passes(h->n, h->d, h->ld, z, src, mode, vec, h->d_partial, h->G, st);
     SGP_HIP_TRY(h, hipGetLastError());
-    if (slot != 0) return enqueue_stats(h, h->d_partial, G, nullptr, w, slot, st);
-    return finish_stats(h, h->d_partial, G, nullptr, w, host_out, per_node_dist_host, st);
+    if (slot != 0) return enqueue_stats(h, h->d_partial, h->G, nullptr, w, slot, st);
+    return finish_stats(h, h->d_partial, h->G, nullptr, w, host_out, per_node_dist_host, st);
 }
 
 int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
@@ -951,6 +958,64 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
     const bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m));
     return run_stats(h, nullptr, src, nest ? 2 : 1, vec, w, host_out, per_node_dist_host,
                      static_cast<hipStream_t>(stream), 0);
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// Statistics without any allocation: the partial table and the row sums live in a file-scope
+// device array.  Every GPU holds its own copy of the array at its own address; the address is
+// looked up once per device and used from then on (the array's name is not a device address in
+// host code).
+// ------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kNoAllocGrid = kStatsGridMax;
+constexpr size_t kNoAllocPartialBytes = (size_t)(SGP_NOALLOC_MAX_NODES + 1) * kNoAllocGrid * sizeof(float);
+constexpr size_t kNoAllocSumsBytes = ((size_t)(SGP_NOALLOC_MAX_NODES + 1) * sizeof(double) + 255) / 256 * 256;
+constexpr size_t kNoAllocScratchBytes = kNoAllocPartialBytes + kNoAllocSumsBytes;
+static_assert(kNoAllocPartialBytes % 256 == 0, "the row sums start on a 256-byte boundary");
+
+constexpr int kNoAllocMaxDevices = 64;
+std::mutex g_noalloc_mutex;
+void *g_noalloc_ptr[kNoAllocMaxDevices];   // device address of this device's copy, once looked up
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char sgp_noalloc_scratch[kNoAllocScratchBytes];
+
+extern "C" {
+
+int sgp_consensus_stats_noalloc(int32_t n, int64_t d, int64_t ld, const float *z, const float *w,
+                                double *out_device, void *stream)
+{
+    if (n < 1 || d < 1 || ld < d || !z || !w || !out_device) return SGP_ERR_INVALID_ARG;
+    if (n > SGP_NOALLOC_MAX_NODES) return SGP_ERR_UNSUPPORTED;   // beyond the fixed scratch array
+    if (!aligned4(z) || !aligned4(w) || (reinterpret_cast<uintptr_t>(out_device) & 7u)) return SGP_ERR_ALIGNMENT;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SGP_ERR_HIP;
+    if (dev < 0 || dev >= kNoAllocMaxDevices) return SGP_ERR_UNSUPPORTED;
+    void *base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+        if (!g_noalloc_ptr[dev]) {
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(sgp_noalloc_scratch)) != hipSuccess || !p) return SGP_ERR_HIP;
+            g_noalloc_ptr[dev] = p;
+        }
+        base = g_noalloc_ptr[dev];
+    }
+    float *partial = static_cast<float *>(base);
+    double *sums = reinterpret_cast<double *>(static_cast<unsigned char *>(base) + kNoAllocPartialBytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec = (ld % 4 == 0) && aligned16(z);
+    // every block of every pass writes its whole column of the table (zeros where it has no
+    // tile), and k_stats_rowsum writes every sum: nothing of the previous call is read
+    launch_stats_passes(n, d, ld, z, StatSource{}, 0, vec, partial, kNoAllocGrid, st);
+    hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, kNoAllocGrid, sums);
+    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, sums, n, w, out_device);
+    if (hipGetLastError() != hipSuccess) return SGP_ERR_HIP;
+    return SGP_OK;
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
