@@ -42,62 +42,101 @@ def algorithmic_bytes_per_update(wl) -> float:
     return total
 
 
-def read_traffic(workload_name):
-    """HBM bytes per launch of the step kernel measured with hardware counters, if a summary for
-    this workload has been committed (profiles/step_kernel_<workload>_pmc.txt or ..._<workload>.txt)."""
-    for name in ("step_kernel_%s_pmc.txt", "step_kernel_%s.txt"):
-        path = os.path.join(ROOT, "profiles", name % workload_name)
-        try:
-            m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
-        except OSError:
-            continue
-        if m:
-            return float(m.group(1))
-    return None
+def read_traffic(workload_name, kernel, n, d, ld):
+    """HBM bytes per launch of the step kernel as hardware counters measured them, read from the
+    committed summary of an EARLIER profiling run (profiles/step_kernel_<workload>_pmc.txt): counters
+    cannot be collected inside a timing run.  Returned with its source only when the summary names
+    the kernel and the shape that this run launched; otherwise (None, None)."""
+    rel = os.path.join("profiles", "step_kernel_%s_pmc.txt" % workload_name)
+    try:
+        text = open(os.path.join(ROOT, rel)).read()
+    except OSError:
+        return None, None
+
+    def field(name):
+        m = re.search(r"^%s:\s*(\S+)" % name, text, re.M)
+        return m.group(1) if m else None
+    if (field("kernel") != kernel or field("n") != str(n) or field("d") != str(d) or field("ld") != str(ld)
+            or field("traffic_bytes_per_launch") is None):
+        return None, None
+    return float(field("traffic_bytes_per_launch")), rel
 
 
-def cpu_baseline(wl, budget_s=15.0):
-    """The oracle as it stands (float32 variant, dense P per coordinate, plus the float64
-    statistics when the workload reports them), timed on the host cores on a contiguous
-    coordinate slice of the workload; coordinates are independent, so the slice is exact."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+FULL_D_LIMIT_BYTES = 16 << 30     # the oracle leg runs at full d when one state array set fits this
+
+
+def _oracle_run(wl, dcols, threads, max_steps, budget_s):
+    """Times `max_steps` oracle iterations (or as many as fit the budget, at least one) of workload
+    wl restricted to its first `dcols` coordinates (coordinates are independent, so that is exact)."""
     import numpy as np
     from oracle import sgp_oracle as O
     from paper_1811_10792_amd import synthetic as syn
-    cores = len(os.sched_getaffinity(0))
-    threads = max(1, min(cores, O.max_threads()))
     O.set_threads(threads)
     n = wl.n
-    dslice = min(wl.d, 1 << 21)
-    x = syn.normal((n, dslice), wl.x_std, wl.seed, 3)
-    u = np.zeros((n, dslice), np.float32)
+    blk = min(dcols, 1 << 21)                       # drawn once, repeated along the row: the values
+    reps = (dcols + blk - 1) // blk                 # do not change what the oracle computes per element
+    x = np.ascontiguousarray(np.tile(syn.normal((n, blk), wl.x_std, wl.seed, 3), (1, reps))[:, :dcols])
+    g = np.ascontiguousarray(np.tile(syn.normal((n, blk), wl.grad_std, wl.seed, 4, 0), (1, reps))[:, :dcols])
+    u = np.zeros((n, dcols), np.float32)
     w = np.ones(n, np.float32)
-    g = syn.normal((n, dslice), wl.grad_std, wl.seed, 4, 0)
-    st = O.OsgpState(n, dslice, np.float32, wl.delay) if wl.delay else None
+    st = O.OsgpState(n, dcols, np.float32, wl.delay) if wl.delay else None
     nest = wl.momentum != 0.0
     adam = wl.optimizer == "adam"
-    v = np.zeros((n, dslice), np.float32) if adam else None
+    v = np.zeros((n, dcols), np.float32) if adam else None
     steps, t0 = 0, time.perf_counter()
     while True:
         if wl.topology == "complete":
             P = np.full((n, n), np.float32(1.0) / np.float32(n), dtype=np.float32)
         else:
             P = O.mixing_matrix(n, wl.peers, steps // max(1, wl.delay), np.float32)
+        ad = O.adam_params(0.9, 0.98, 1e-8, steps + 1, np.float32) if adam else None
         if wl.delay:
             z = O.step_osgp(P, x, w, u if (nest or adam) else None, g, wl.gamma, wl.momentum, st, steps,
-                            nesterov=nest, adam=O.adam_params(0.9, 0.98, 1e-8, steps + 1, np.float32) if adam else None, v=v)
+                            nesterov=nest, adam=ad, v=v)
         else:
             z = O.step(P, x, w, u if (nest or adam) else None, g, wl.gamma, wl.momentum, nesterov=nest,
-                       adam=O.adam_params(0.9, 0.98, 1e-8, steps + 1, np.float32) if adam else None, v=v)
+                       adam=ad, v=v)
         if wl.stats_each_step:
             O.consensus_stats(z, w)
+        del z
         steps += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or steps >= 50:
+        if el >= budget_s or steps >= max_steps:
             break
-    return {"value": n * dslice * steps / el, "unit": "node-param updates/s", "cores": threads,
-            "kind": "oracle",
-            "sample": "%d steps of %s on a contiguous slice of %d of its %d coordinates per node, "
-                      "all %d nodes, %.1f s" % (steps, wl.name, dslice, wl.d, n, el)}
+    return n * dcols * steps / el, steps, el
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands (float32 variant, dense P per coordinate, plus the float64
+    statistics when the workload reports them) timed on the host: with all cores at the workload's
+    full size when the state fits the host comfortably (every configuration but the Transformer-sized
+    ones, which run on a slice of 2^21 coordinates per node), and with one core on a slice."""
+    from oracle import sgp_oracle as O
+    cores = len(os.sched_getaffinity(0))
+    threads = max(1, min(cores, O.max_threads()))
+    arrays = 5 if wl.optimizer == "adam" else 4
+    full = wl.n * wl.d * 4 * arrays <= FULL_D_LIMIT_BYTES
+    dcols = wl.d if full else min(wl.d, 1 << 21)
+    value, steps, el = _oracle_run(wl, dcols, threads, max_steps=3 if dcols > (1 << 22) else 50, budget_s=12.0)
+    d1 = min(wl.d, 1 << 19)
+    v1, s1, e1 = _oracle_run(wl, d1, 1, max_steps=3 if wl.n * d1 > (1 << 22) else 50, budget_s=6.0)
+    what = ("all %d coordinates per node" % wl.d) if full else \
+        ("a contiguous slice of %d of its %d coordinates per node" % (dcols, wl.d))
+    return {"value": value, "unit": "node-param updates/s", "cores": threads, "kind": "oracle",
+            "sample": "%d steps of %s on %s, all %d nodes, %.1f s" % (steps, wl.name, what, wl.n, el),
+            "single_core": {"value": v1, "cores": 1,
+                            "sample": "%d steps on a contiguous slice of %d coordinates per node, %.1f s" % (s1, d1, e1)},
+            "cpu_model": cpu_model()}
 
 
 def main():
@@ -122,6 +161,10 @@ def main():
                     help="regions: carve the state arrays out of one arena so that the written "
                          "streams x, u, z sit in different HBM regions (found by timing); "
                          "default: plain allocations")
+    ap.add_argument("--no-default-placement", action="store_true",
+                    help="skip the extra leg that repeats the steps with ordinary allocations")
+    ap.add_argument("--strict-placement", action="store_true",
+                    help="exit non-zero when the region-aware placement was asked for but is degraded")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run the library's plain copy kernel over one state array (a transfer of "
                          "known size, against which hardware traffic counters are scaled)")
@@ -161,10 +204,23 @@ def main():
 
     pipelined = do_stats and not args.separate_stats and not args.sync_stats and wl.optimizer != "adam"
 
+    pending = [0]           # statistics enqueued and not yet fetched
+
+    def drain():
+        r = None
+        while pending[0]:
+            r = eng.step_stats_end()
+            pending[0] -= 1
+        return r
+
     def one_step(k):
         if pipelined:       # enqueue step k, then pick up the statistics of step k-1
             eng.step_stats_begin(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k)
-            return eng.step_stats_end() if k > 0 else None
+            pending[0] += 1
+            if pending[0] < 2:
+                return None
+            pending[0] -= 1
+            return eng.step_stats_end()
         if adam:
             eng.step_adam(X, W, U, V2, pool[k % len(pool)], Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
             return eng.consensus_stats(Z, W) if do_stats else None
@@ -213,33 +269,42 @@ def main():
         k += 1
     if args.calibrate_copy:
         sgp.sgp_copy(Z, pool[0])          # n*ld*4 bytes read, n*ld*4 bytes written
-        torch.cuda.synchronize()
-    # HIP events around the step kernel, recorded by the library on the stream it launches on
-    eng.set_kernel_timing(True)
-    kern_ms = []
     torch.cuda.synchronize()
+
+    # ---- the timed region: exactly --steps steps, nothing but the steps ------------------------
     t0 = time.perf_counter()
     for i in range(args.steps):
         last = one_step(k)
         k += 1
-        if i % 32 == 31:
-            kern_ms += eng.step_kernel_times()
     if pipelined:
-        last = eng.step_stats_end()       # the last step's statistics, inside the timed region
+        last = drain()                    # the last step's statistics, inside the timed region
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    kernel_name = eng.last_step_kernel()  # what the library launched, as it reports it
+
+    # ---- a second pass of the same steps for the roofline of the dominant kernel: HIP events
+    # around the step kernel, recorded by the library on the stream it launches on (kept out of the
+    # timed region above, where the two extra event records per step would be part of the step)
+    eng.set_kernel_timing(True)
+    kern_ms = []
+    ksteps = min(args.steps, 60)
+    for i in range(ksteps):
+        one_step(k)
+        k += 1
+        if i % 32 == 31:
+            kern_ms += eng.step_kernel_times()
+    drain()
+    torch.cuda.synchronize()
     kern_ms += eng.step_kernel_times()
-    assert len(kern_ms) == args.steps, (len(kern_ms), args.steps)
+    eng.set_kernel_timing(False)
+    assert len(kern_ms) == ksteps, (len(kern_ms), ksteps)
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
     bpu = algorithmic_bytes_per_update(wl)
-    fused = (do_stats and not args.separate_stats and wl.peers == 1 and not wl.delay and n <= 32
-             and d % 4 == 0 and not complete)
-    kernel_name = ("k_step_one_peer_stats (step + consensus statistics in one kernel)" if fused else
-                   "k_step_complete" if complete else
-                   "k_step_delay" if wl.delay == 1 else
-                   "k_step_delay every %d-th iteration, k_step_one_peer otherwise" % wl.delay if wl.delay else
-                   "k_step_gather" if wl.peers > 1 else "k_step_one_peer")
     achieved = bpu * n * d / avg_kern_s / 1e9
+    whole = bpu * n * d * args.steps / elapsed / 1e9
+    traffic, traffic_source = read_traffic(wl.name, kernel_name, n, d, ld)
+    placement = alloc.describe()
+    degraded = args.placement == "regions" and not (placement["mode"] == "regions" and placement.get("structured"))
     out = {
         "metric": "SGP node-param updates/sec (n*d/step time) + achieved HBM GB/s vs peak",
         "value": n * d * args.steps / elapsed,
@@ -254,13 +319,19 @@ def main():
                    "consensus_stats_each_step": bool(do_stats),
                    "stats_fetch": ("one step late" if pipelined else "every step") if do_stats else None,
                    "gradient_pool": len(pool),
-                   "placement": alloc.describe()},
+                   "placement": placement},
+        # True: the region-aware placement was asked for but the arena could not be had or its probe
+        # found no region structure, so the arrays sit wherever the allocator put them
+        "placement_degraded": bool(degraded),
         "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_update": bpu,
                      "kernel_ms_avg": avg_kern_s * 1e3, "kernel_ms_median": sorted(kern_ms)[len(kern_ms) // 2],
-                     "kernel_ms_min": min(kern_ms)},
+                     "kernel_ms_min": min(kern_ms), "kernel_timing": "separate pass of %d steps" % ksteps,
+                     # the whole step as the timed region saw it (every launch, gap and copy included)
+                     "whole_step_achieved": whole, "whole_step_frac": whole / HBM_PEAK_GBPS},
     }
     if last is not None:
         out["consensus_dist_max_last"] = last.dist_max
@@ -272,9 +343,62 @@ def main():
     eng.close()
     del X, U, Z, V2, pool, alloc
     torch.cuda.empty_cache()
+    if args.placement == "regions" and not args.no_default_placement:
+        out["default_placement"] = default_placement_leg(wl, ld, args, bpu)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
+    if degraded and args.strict_placement:
+        sys.exit("bench.py: region-aware placement was requested but is degraded (see placement_degraded)")
+
+
+def default_placement_leg(wl, ld, args, bpu):
+    """The same steps with ordinary back-to-back allocations (what a caller gets who hands the
+    library whatever the allocator returned), reported beside the region-aware figure."""
+    import torch
+    import paper_1811_10792_amd as sgp
+    from paper_1811_10792_amd import synthetic as syn
+    n, d = wl.n, wl.d
+    nest = wl.momentum != 0.0
+    adam = wl.optimizer == "adam"
+    eng = sgp.SGP(n, d, ld, topology=1 if wl.topology == "complete" else 0, peers=wl.peers, delay=wl.delay)
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3)
+    U = torch.zeros((n, ld), dtype=torch.float32, device="cuda")
+    V2 = torch.zeros((n, ld), dtype=torch.float32, device="cuda") if adam else None
+    W = torch.ones(n, dtype=torch.float32, device="cuda")
+    Z = torch.empty((n, ld), dtype=torch.float32, device="cuda")
+    pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i) for i in range(max(1, args.pool))]
+    do_stats = wl.stats_each_step and not args.no_stats
+    pipelined = do_stats and not adam
+
+    def one_step(k):
+        G = pool[k % len(pool)]
+        if pipelined:
+            eng.step_stats_begin(X, W, U if nest else None, G, Z, wl.gamma, wl.momentum, k)
+            if k > 0:
+                eng.step_stats_end()
+        elif adam:
+            eng.step_adam(X, W, U, V2, G, Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
+        else:
+            eng.step(X, W, U if nest else None, G, Z, wl.gamma, wl.momentum, k)
+    k = 0
+    for _ in range(max(2, args.warmup)):
+        one_step(k)
+        k += 1
+    torch.cuda.synchronize()
+    steps = max(1, min(args.steps, 20))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step(k)
+        k += 1
+    if pipelined:
+        eng.step_stats_end()
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    eng.close()
+    whole = bpu * n * d * steps / el / 1e9
+    return {"ms_per_step": el / steps * 1e3, "steps": steps, "value": n * d * steps / el,
+            "whole_step_frac": whole / HBM_PEAK_GBPS}
 
 
 if __name__ == "__main__":

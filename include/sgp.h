@@ -58,6 +58,8 @@ extern "C" {
 #define SGP_TOPO_CUSTOM 2       /* caller-supplied sparse rows of P, see sgp_set_mixing */
 
 #define SGP_MAX_NODES 1024 /* largest n accepted by sgp_create */
+#define SGP_MAX_NODES_GATHER 600 /* largest n for more than one peer without delay and for custom rows
+                                    (128-bit accesses up to n = 150, scalar ones beyond) */
 #define SGP_MAX_PEERS 16   /* largest peers accepted by sgp_create */
 #define SGP_MAX_DELAY 64   /* largest delay (tau) accepted by sgp_create */
 
@@ -129,7 +131,7 @@ int sgp_set_topology(sgp_handle *h, int32_t topology, int32_t peers);
  *   in_weight [n][entries] host : p_{i,j} of that entry
  * Receiver i computes sum_q fl(in_weight * xh_j) over its used entries in the order given (list
  * senders in ascending index to reproduce a dense row-times-vector product).  The arrays are copied;
- * may be called again between steps (time-varying P).  n <= 256 (n <= 64 on the 128-bit path).
+ * may be called again between steps (time-varying P).  n <= SGP_MAX_NODES_GATHER.
  * Errors: SGP_ERR_INVALID_ARG (null, entries < 1 or > n, index out of range), SGP_ERR_NOMEM,
  * SGP_ERR_HIP.  sgp_step on a custom handle without mixing rows returns SGP_ERR_SEQUENCE.
  */
@@ -174,7 +176,12 @@ int sgp_reset(sgp_handle *h);
  * nothing is launched).  Messages sent at the last sending iteration stay in the library's
  * buffers.
  * Errors: SGP_ERR_INVALID_ARG, SGP_ERR_ALIGNMENT, SGP_ERR_SEQUENCE, SGP_ERR_UNSUPPORTED (more
- * than one peer without delay and n > 256), SGP_ERR_NOMEM, SGP_ERR_HIP.
+ * than one peer without delay, or caller-supplied rows, and n > SGP_MAX_NODES_GATHER: those modes
+ * keep one LDS column of n values per work-item), SGP_ERR_NOMEM, SGP_ERR_HIP.  A call that returns
+ * an error has not modified x, w, m or z_out.
+ * The push-sum weights are updated by the step kernel itself: w holds w^(k) until the kernel's last
+ * block has finished and w^(k+1) afterwards; one call is one kernel launch (two when d % 4 != 0 or
+ * an array is not 16-byte aligned).
  */
 int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
              float gamma, float momentum, int64_t k, void *stream);
@@ -296,6 +303,12 @@ const char *sgp_status_string(int status);
 
 /* hipError_t value of the last failed HIP call on this handle (0 if none). */
 int sgp_last_hip_error(const sgp_handle *h);
+
+/* Measurement utility: static name of the step kernel that the latest successful step on this
+ * handle launched ("k_step_one_peer", "k_step_one_peer_stats", "k_step_gather", "k_step_complete",
+ * "k_step_delay", "k_step_delay2"; "" before the first step), so that a benchmark can report what
+ * ran instead of re-deriving the library's dispatch. */
+const char *sgp_last_step_kernel(const sgp_handle *h);
 
 /*
  * Measurement utility.  With timing enabled, sgp_step brackets its fused step kernel (not the

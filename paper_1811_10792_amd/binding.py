@@ -24,6 +24,7 @@ SGP_ERR_NOMEM = -6
 SGP_TOPO_DIRECTED_EXP = 0
 SGP_TOPO_COMPLETE = 1
 SGP_TOPO_CUSTOM = 2
+SGP_MAX_NODES_GATHER = 600
 
 # every symbol include/sgp.h declares
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
@@ -32,7 +33,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
-           "sgp_consensus_stats_noalloc")
+           "sgp_consensus_stats_noalloc", "sgp_last_step_kernel")
 
 
 class SgpError(RuntimeError):
@@ -99,8 +100,10 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_consensus_stats_noalloc.argtypes = [i32, i64, i64, vp, vp, vp, vp]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
+    lib.sgp_last_step_kernel.argtypes = [vp]
+    lib.sgp_last_step_kernel.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name != "sgp_status_string":
+        if name not in ("sgp_status_string", "sgp_last_step_kernel"):
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -318,6 +321,10 @@ class SGP:
         _check(self._lib.sgp_step_kernel_times(self._h, ctypes.addressof(buf), 64, ctypes.byref(cnt)),
                "sgp_step_kernel_times")
         return list(buf[:cnt.value])
+
+    def last_step_kernel(self) -> str:
+        """Name of the step kernel the latest successful step launched."""
+        return self._lib.sgp_last_step_kernel(self._h).decode()
 
     def reset(self) -> None:
         _check(self._lib.sgp_reset(self._h), "sgp_reset")

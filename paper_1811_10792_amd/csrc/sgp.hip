@@ -14,16 +14,18 @@
 //
 // Layout of the sources (one translation unit; the .inc files are included below):
 //   schedule.inc            host peer scheduler of the directed exponential graph
-//   device_common.inc       128-bit access helpers, local optimiser step, launch constants
+//   device_common.inc       128-bit access helpers, local optimiser step, push-sum weight update
+//                           inside the step kernels, launch constants
 //   step_one_peer.inc       one out-peer: walk over the cycles of the shift
 //   step_stats_kernel.inc   the same walk with the consensus statistics taken from registers
 //   step_gather.inc         several out-peers / caller-supplied rows: private LDS columns
 //   step_complete.inc       complete graph
 //   step_overlap.inc        tau-overlap SGP: own share now, messages of the previous round
-//   weights.inc             push-sum weight kernels, stand-alone de-bias, reference copy
+//   weights.inc             stand-alone de-bias, reference copy
 //   stats.inc               stand-alone consensus statistics and the final reductions
 //   sgp.hip                 handle, launchers, C ABI
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstdint>
@@ -81,6 +83,12 @@ constexpr int kStatsCache = 32;   // nodes whose z the small-n statistics kernel
 // ------------------------------------------------------------------------------------------
 // Handle
 // ------------------------------------------------------------------------------------------
+namespace {
+constexpr int kStatsGridMax = 2048;
+constexpr int kResultSlots = 3;   // statistics results: one synchronous, two in flight
+constexpr int kStepCounters = (1 + kCountLines) * kCountStride;   // the step kernels' counters of finished blocks
+}  // namespace
+
 struct sgp_handle {
     int n;
     int64_t d, ld;
@@ -92,24 +100,27 @@ struct sgp_handle {
     bool dev_ready;
     bool biased;        // z = x instead of x / w (ablation without the push-sum weight)
     int *d_tab;         // [max(L,1)][n][S] sorted source lists, one table per k mod L
-    bool tab_stale;     // topology or peer count changed: rebuild d_tab before the next step
     int cS;             // caller-supplied mixing rows (SGP_TOPO_CUSTOM): entries per row, 0 = not set
     int *d_cidx;        // [n][cS] senders, -1 = padding
     float *d_cw;        // [n][cS] weights
-    int *d_unit_w;      // 1 if every push-sum weight equals 1 after the latest weight update
-    float *d_w_old;     // [n] the weights before the latest update (weight decay on x / w)
+    unsigned *d_done;   // counters of finished blocks: the step kernels' (kStepCounters), then one per result slot
     float wd;           // weight decay coefficient, 0 = off
     bool wd_on_x;       // decay acts on the numerator instead of the de-biased parameters
-    float *d_partial;   // [(n+1)][G] partial sums of the statistics
-    float *d_partial_f; // [(n+1)][Gf] partial sums written by the fused step+statistics kernel
-    size_t partial_f_elems;
+    float *d_partial;   // [(n+1)][G] partial sums of the stand-alone statistics
     int G;
-    double *d_sums;     // [n+1] per-node sums of squares (+ the average's), or the fused kernel's
-                        // [kSlotSumBlocks][33] block sums
+    double *d_sums;     // [n+1] per-node sums of squares (+ the average's) of the stand-alone statistics
+    // the fused step+statistics kernel, per result slot: its partial table [33][Gf], the block sums
+    // of the reduction [kSlotSumBlocks][33] and a copy of the weights the step produced
+    float *d_partial_f[kResultSlots];
+    double *d_sums_f[kResultSlots];
+    float *d_w_snap[kResultSlots];
+    bool fused_ready;
+    hipStream_t side;       // the reduction of the fused statistics runs here, beside the next step
+    hipEvent_t ev_step[kResultSlots];   // step kernel of the slot finished (recorded on the caller's stream)
     double *d_result;   // [kResultSlots][8 + n]: slot 0 for the synchronous calls, 1.. for begin/end
     double *h_result;   // pinned mirror
-    hipEvent_t ev_res[2];   // results of sgp_step_stats_begin copied to the host
-    bool ev_res_made;
+    hipEvent_t ev_res[kResultSlots];    // result of the slot copied to the host
+    bool ev_made;
     int pend_head, pend_count;   // ring of outstanding begin/end results (slots 1 + index)
     float *d_msg[2];    // overlap mode: pre-weighted messages p*xh_j, [n][ld] each
     bool msg_external;  // d_msg points into caller-owned memory
@@ -118,18 +129,16 @@ struct sgp_handle {
     bool have_msgs;
     int64_t last_k;
     int last_hip;
+    const char *last_kernel;              // name of the step kernel of the latest successful step
 
     bool timing;                          // bracket the step kernel with events
     hipEvent_t ev[SGP_TIMING_RING][2];
-    bool ev_made;
+    bool ev_timing_made;
     int64_t ev_head;                      // timed steps recorded so far
     int64_t ev_read;                      // timed steps already reported
 };
 
 namespace {
-
-constexpr int kStatsGridMax = 2048;
-constexpr int kResultSlots = 3;   // statistics results: one synchronous, two in flight
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
@@ -137,7 +146,7 @@ bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0
 int hip_fail(sgp_handle *h, hipError_t e)
 {
     if (h) h->last_hip = (int)e;
-    return SGP_ERR_HIP;
+    return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : SGP_ERR_HIP;
 }
 
 #define SGP_HIP_TRY(h, expr)                           \
@@ -167,74 +176,118 @@ void build_tables(const sgp_handle *h, int *tab)
 }
 
 // (Re)builds the source tables of the directed exponential graph for the handle's current peers.
+// The new table is complete before the old one is released, so a failure leaves the handle as it was.
 int upload_tables(sgp_handle *h)
 {
-    if (h->d_tab) {
-        (void)hipFree(h->d_tab);   // waits for the kernels that still read it
-        h->d_tab = nullptr;
-    }
     const int n = h->n, S = h->S, tables = h->L > 0 ? h->L : 1;
     size_t tab_elems = (size_t)tables * n * S;
     int *host_tab = static_cast<int *>(std::malloc(tab_elems * sizeof(int)));
     if (!host_tab) return SGP_ERR_NOMEM;
     build_tables(h, host_tab);
-    hipError_t e = hipMalloc(&h->d_tab, tab_elems * sizeof(int));
-    if (e == hipSuccess)
-        e = hipMemcpy(h->d_tab, host_tab, tab_elems * sizeof(int), hipMemcpyHostToDevice);
+    int *fresh = nullptr;
+    hipError_t e = hipMalloc(&fresh, tab_elems * sizeof(int));
+    if (e == hipSuccess) e = hipMemcpy(fresh, host_tab, tab_elems * sizeof(int), hipMemcpyHostToDevice);
     std::free(host_tab);
-    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
-    h->tab_stale = false;
+    if (e != hipSuccess) {
+        if (fresh) (void)hipFree(fresh);
+        return hip_fail(h, e);
+    }
+    if (h->d_tab) (void)hipFree(h->d_tab);   // waits for the kernels that still read it
+    h->d_tab = fresh;
     return SGP_OK;
 }
 
+// Device resources every launching call needs.  Each pointer is allocated once: a call that failed
+// half way is picked up where it stopped.
 int ensure_device(sgp_handle *h)
 {
-    if (h->dev_ready) return h->tab_stale ? upload_tables(h) : SGP_OK;
+    if (h->dev_ready) return SGP_OK;
     const int n = h->n;
-    int rc = upload_tables(h);
-    if (rc != SGP_OK) return rc;
-    hipError_t e;
-
+    if (!h->d_tab) {
+        int rc = upload_tables(h);
+        if (rc != SGP_OK) return rc;
+    }
     h->G = kStatsGridMax;
-    e = hipMalloc(&h->d_unit_w, sizeof(int));
-    if (e == hipSuccess) e = hipMalloc(&h->d_w_old, (size_t)n * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&h->d_sums,
-                                       (size_t)std::max(n + 1, kSlotSumBlocks * (kStatsCache + 1)) * sizeof(double));
-    if (e == hipSuccess) e = hipMalloc(&h->d_result, (size_t)kResultSlots * (8 + n) * sizeof(double));
-    if (e == hipSuccess)
-        e = hipHostMalloc(reinterpret_cast<void **>(&h->h_result), (size_t)kResultSlots * (8 + n) * sizeof(double),
-                          hipHostMallocDefault);
-    if (e == hipSuccess && h->delay) {
+    const size_t res_bytes = (size_t)kResultSlots * (8 + n) * sizeof(double);
+    if (!h->d_done) {
+        SGP_HIP_TRY(h, hipMalloc(&h->d_done, (kStepCounters + kResultSlots) * sizeof(unsigned)));
+        SGP_HIP_TRY(h, hipMemset(h->d_done, 0, (kStepCounters + kResultSlots) * sizeof(unsigned)));
+    }
+    if (!h->d_partial) SGP_HIP_TRY(h, hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float)));
+    if (!h->d_sums) SGP_HIP_TRY(h, hipMalloc(&h->d_sums, (size_t)(n + 1) * sizeof(double)));
+    if (!h->d_result) SGP_HIP_TRY(h, hipMalloc(&h->d_result, res_bytes));
+    if (!h->h_result)
+        SGP_HIP_TRY(h, hipHostMalloc(reinterpret_cast<void **>(&h->h_result), res_bytes, hipHostMallocDefault));
+    if (h->delay) {
         size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
-        for (int b = 0; b < 2 && e == hipSuccess; ++b) {
-            if (!h->msg_external) e = hipMalloc(&h->d_msg[b], bytes);
-            if (e == hipSuccess) e = hipMalloc(&h->d_msgw[b], (size_t)n * sizeof(float));
+        for (int b = 0; b < 2; ++b) {
+            if (!h->msg_external && !h->d_msg[b]) SGP_HIP_TRY(h, hipMalloc(&h->d_msg[b], bytes));
+            if (!h->d_msgw[b]) SGP_HIP_TRY(h, hipMalloc(&h->d_msgw[b], (size_t)n * sizeof(float)));
         }
     }
-    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
     h->dev_ready = true;
+    return SGP_OK;
+}
+
+unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1) / block); }
+
+// Whether a step with statistics can take them inside the step kernel.
+bool fused_stats_applies(const sgp_handle *h, bool gather, bool complete, bool custom, bool adam, bool vec,
+                         long tail)
+{
+    return h->delay == 0 && !gather && !complete && !custom && !adam && h->n <= kStatsCache && vec && tail == 0;
+}
+
+// Resources of the fused step+statistics path: a stream of its own for the reduction, events, and
+// per result slot the partial table, the block sums and the weight copy.  Allocated once, before
+// anything of the step that needs them is launched.
+int ensure_fused(sgp_handle *h)
+{
+    if (h->fused_ready) return SGP_OK;
+    const unsigned Gf = grid_for((long)(h->d / 4), kStatsStepBlock);
+    if (!h->side) SGP_HIP_TRY(h, hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
+    for (int s = 0; s < kResultSlots; ++s) {
+        if (!h->d_partial_f[s])
+            SGP_HIP_TRY(h, hipMalloc(&h->d_partial_f[s], (size_t)(kStatsCache + 1) * Gf * sizeof(float)));
+        if (!h->d_sums_f[s])
+            SGP_HIP_TRY(h, hipMalloc(&h->d_sums_f[s], (size_t)kSlotSumBlocks * (kStatsCache + 1) * sizeof(double)));
+        if (!h->d_w_snap[s]) SGP_HIP_TRY(h, hipMalloc(&h->d_w_snap[s], (size_t)h->n * sizeof(float)));
+    }
+    h->fused_ready = true;
+    return SGP_OK;
+}
+
+int ensure_result_events(sgp_handle *h)
+{
+    if (h->ev_made) return SGP_OK;
+    for (int s = 0; s < kResultSlots; ++s) {
+        if (!h->ev_step[s]) SGP_HIP_TRY(h, hipEventCreate(&h->ev_step[s]));
+        if (!h->ev_res[s]) SGP_HIP_TRY(h, hipEventCreateWithFlags(&h->ev_res[s], hipEventDisableTiming));
+    }
+    h->ev_made = true;
     return SGP_OK;
 }
 
 void release_device(sgp_handle *h)
 {
-    if (h->ev_made)
+    if (h->ev_timing_made)
         for (int i = 0; i < SGP_TIMING_RING; ++i) {
-            (void)hipEventDestroy(h->ev[i][0]);
-            (void)hipEventDestroy(h->ev[i][1]);
+            if (h->ev[i][0]) (void)hipEventDestroy(h->ev[i][0]);
+            if (h->ev[i][1]) (void)hipEventDestroy(h->ev[i][1]);
         }
-    if (h->ev_res_made) {
-        (void)hipEventDestroy(h->ev_res[0]);
-        (void)hipEventDestroy(h->ev_res[1]);
+    for (int s = 0; s < kResultSlots; ++s) {
+        if (h->ev_step[s]) (void)hipEventDestroy(h->ev_step[s]);
+        if (h->ev_res[s]) (void)hipEventDestroy(h->ev_res[s]);
+        if (h->d_partial_f[s]) (void)hipFree(h->d_partial_f[s]);
+        if (h->d_sums_f[s]) (void)hipFree(h->d_sums_f[s]);
+        if (h->d_w_snap[s]) (void)hipFree(h->d_w_snap[s]);
     }
+    if (h->side) (void)hipStreamDestroy(h->side);
     if (h->d_tab) (void)hipFree(h->d_tab);
     if (h->d_cidx) (void)hipFree(h->d_cidx);
     if (h->d_cw) (void)hipFree(h->d_cw);
-    if (h->d_unit_w) (void)hipFree(h->d_unit_w);
-    if (h->d_w_old) (void)hipFree(h->d_w_old);
+    if (h->d_done) (void)hipFree(h->d_done);
     if (h->d_partial) (void)hipFree(h->d_partial);
-    if (h->d_partial_f) (void)hipFree(h->d_partial_f);
     if (h->d_sums) (void)hipFree(h->d_sums);
     if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
@@ -244,47 +297,57 @@ void release_device(sgp_handle *h)
     }
 }
 
-unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1) / block); }
-
 struct StepArgs {
     float *x, *u, *z;
-    const float *g, *w;
-    const int *unit_w;
+    const float *g;
+    WeightOp wop;
     int n;
     size_t ld;
     float p;
     Hyper hp;
     hipStream_t stream;
+    const char **name;    // receives the name of the kernel launched
 };
 
 template <int V, int OPT, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
     hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
-                       dim3(kOpBlock), 0,
-                       a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, h,
+                       dim3(kOpBlock), weight_lds_bytes(a.n),
+                       a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols, h,
                        len, a.p, a.hp);
+    *a.name = "k_step_one_peer";
 }
+
+// LDS of the gather kernel: the two weight arrays, then one private column of n values per work-item.
+size_t gather_lds_bytes(int n, int V) { return weight_lds_bytes(n) + (size_t)n * kGatherBlock * V * sizeof(float); }
 
 template <int V, int OPT, bool ZOUT>
 void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S)
 {
-    size_t lds = (size_t)a.n * kGatherBlock * V * sizeof(float);
+    const size_t lds = gather_lds_bytes(a.n, V);
     dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
-    if (tabw)
-        hipLaunchKernelGGL((k_step_gather<V, OPT, ZOUT, true>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
-    else
-        hipLaunchKernelGGL((k_step_gather<V, OPT, ZOUT, false>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, tab, tabw, S, a.p, a.hp);
+    auto go = [&](auto kernel) {
+        // more than 64 KiB of dynamic LDS has to be asked for per kernel (a failure shows up as the
+        // launch error that the caller checks)
+        if (lds > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kernel, grid, block, lds, a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols,
+                           tab, tabw, S, a.p, a.hp);
+    };
+    if (tabw) go(k_step_gather<V, OPT, ZOUT, true>);
+    else go(k_step_gather<V, OPT, ZOUT, false>);
+    *a.name = "k_step_gather";
 }
 
 template <int V, int OPT, bool ZOUT>
 void launch_complete(const StepArgs &a, size_t col0, long ncols)
 {
     hipLaunchKernelGGL((k_step_complete<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
-                       0, a.stream, a.x, a.u, a.g, a.z, a.w, a.unit_w, a.n, a.ld, col0, ncols, a.p,
+                       weight_lds_bytes(a.n), a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols, a.p,
                        a.hp);
+    *a.name = "k_step_complete";
 }
 
 template <int V, int OPT, bool ZOUT>
@@ -292,32 +355,35 @@ void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_p
                   const int *tab_prev, int S, int ha, int hb)
 {
     dim3 grid(grid_for(ncols, kDelayBlock * kDelayCols)), block(kDelayBlock);
+    const size_t lds = weight_lds_bytes(a.n);
     const int nm = tab_prev ? S - 1 : 0;
     if (nm == 2 && SGP_DELAY_WINDOW) {   // two messages: each message row is loaded once
         const int stride = ((hb - ha) % a.n + a.n) % a.n;
         const int len = a.n / gcd_int(a.n, stride);
-        hipLaunchKernelGGL((k_step_delay2<V, OPT, ZOUT>), grid, block, 0, a.stream, a.x, a.u, a.g, a.z,
-                           a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, ha, hb, stride, len,
+        hipLaunchKernelGGL((k_step_delay2<V, OPT, ZOUT>), grid, block, lds, a.stream, a.x, a.u, a.g, a.z,
+                           a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, ha, hb, stride, len,
                            a.p, a.hp);
+        *a.name = "k_step_delay2";
         return;
     }
+    *a.name = "k_step_delay";
     if (nm == 0)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 0>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 0>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
     else if (nm == 1)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 1>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 1>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
 #if !SGP_DELAY_WINDOW
     else if (nm == 2)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 2>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 2>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
 #endif
     else
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, -1>), grid, block, 0, a.stream, a.x, a.u, a.g,
-                           a.z, a.w, a.unit_w, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
+        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, -1>), grid, block, lds, a.stream, a.x, a.u, a.g,
+                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
                            a.p, a.hp);
 }
 
@@ -383,6 +449,7 @@ int sgp_create(sgp_handle **out, int32_t n, int64_t d, int64_t ld, int32_t topol
     h->distinct = s.distinct;
     h->S = s.distinct + 1;
     h->last_k = -1;
+    h->last_kernel = "";
     *out = h;
     return SGP_OK;
 }
@@ -391,12 +458,12 @@ int sgp_destroy(sgp_handle *h)
 {
     if (!h) return SGP_OK;
     int rc = SGP_OK;
-    if (h->dev_ready) {
+    // also after a set-up that failed half way, or mixing rows set on a handle that never stepped:
+    // every pointer is checked on its own
+    if (h->dev_ready || h->side || h->d_tab || h->d_cidx) {
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) rc = SGP_ERR_HIP;
     }
-    // also after a set-up that failed half way, or mixing rows set on a handle that never stepped:
-    // every pointer is checked on its own
     release_device(h);
     delete h;
     return rc;
@@ -416,13 +483,25 @@ int sgp_set_topology(sgp_handle *h, int32_t topology, int32_t peers)
     if (topology != SGP_TOPO_DIRECTED_EXP && topology != SGP_TOPO_COMPLETE && topology != SGP_TOPO_CUSTOM)
         return SGP_ERR_UNSUPPORTED;
     if (h->delay != 0) return SGP_ERR_UNSUPPORTED;
+    const int old_topology = h->topology, old_peers = h->peers;
     h->topology = topology;
     h->peers = peers;
     Schedule s = make_schedule(h->n, peers, 0);
     h->L = s.L;
     h->distinct = s.distinct;
     h->S = s.distinct + 1;
-    h->tab_stale = true;
+    if (h->d_tab && peers != old_peers) {   // tables exist: rebuild them now, not inside a step
+        int rc = upload_tables(h);
+        if (rc != SGP_OK) {                 // the old tables are still in place: keep the old setting
+            h->topology = old_topology;
+            h->peers = old_peers;
+            s = make_schedule(h->n, old_peers, 0);
+            h->L = s.L;
+            h->distinct = s.distinct;
+            h->S = s.distinct + 1;
+            return rc;
+        }
+    }
     return SGP_OK;
 }
 
@@ -432,20 +511,22 @@ int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight,
     const size_t cnt = (size_t)h->n * entries;
     for (size_t q = 0; q < cnt; ++q)
         if (in_idx[q] < -1 || in_idx[q] >= h->n) return SGP_ERR_INVALID_ARG;
-    if (h->d_cidx) {   // hipFree waits for the kernels that still read the old rows
-        (void)hipFree(h->d_cidx);
-        h->d_cidx = nullptr;
+    // the new rows are complete before the old ones are released
+    int *idx = nullptr;
+    float *wts = nullptr;
+    hipError_t e = hipMalloc(&idx, cnt * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc(&wts, cnt * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(idx, in_idx, cnt * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(wts, in_weight, cnt * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        if (idx) (void)hipFree(idx);
+        if (wts) (void)hipFree(wts);
+        return hip_fail(h, e);
     }
-    if (h->d_cw) {
-        (void)hipFree(h->d_cw);
-        h->d_cw = nullptr;
-    }
-    h->cS = 0;
-    hipError_t e = hipMalloc(&h->d_cidx, cnt * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc(&h->d_cw, cnt * sizeof(float));
-    if (e == hipSuccess) e = hipMemcpy(h->d_cidx, in_idx, cnt * sizeof(int), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(h->d_cw, in_weight, cnt * sizeof(float), hipMemcpyHostToDevice);
-    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
+    if (h->d_cidx) (void)hipFree(h->d_cidx);   // hipFree waits for the kernels that still read the old rows
+    if (h->d_cw) (void)hipFree(h->d_cw);
+    h->d_cidx = idx;
+    h->d_cw = wts;
     h->cS = entries;
     return SGP_OK;
 }
@@ -469,7 +550,7 @@ int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1)
 {
     if (!h || !buf0 || !buf1 || buf0 == buf1 || !h->delay || !aligned16(buf0) || !aligned16(buf1))
         return SGP_ERR_INVALID_ARG;
-    if (h->dev_ready) return SGP_ERR_SEQUENCE;
+    if (h->dev_ready || (h->d_msg[0] && !h->msg_external)) return SGP_ERR_SEQUENCE;
     h->d_msg[0] = buf0;
     h->d_msg[1] = buf1;
     h->msg_external = true;
@@ -479,6 +560,8 @@ int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1)
 }
 
 int sgp_last_hip_error(const sgp_handle *h) { return h ? h->last_hip : 0; }
+
+const char *sgp_last_step_kernel(const sgp_handle *h) { return h ? h->last_kernel : ""; }
 
 int sgp_schedule(int32_t n, int32_t peers, int64_t k, int32_t *out_peers, int32_t *in_peers,
                  float *weight)
@@ -517,14 +600,12 @@ int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_
 }
 
 // What step_impl did about the statistics: G > 0 means the fused kernel ran and left its partial
-// table (G blocks) in h->d_partial_f for a walk with this hop and cycle length.
+// table (G blocks) in the slot's table for a walk with this hop and cycle length.
 struct FusedStats {
+    int slot = 0;   // in: result slot whose table and weight copy the fused kernel may use
     int G = 0, hop = 0, len = 1;
 };
 
-// One iteration; with fused != NULL the caller wants the statistics of z^(k+1) as well: when the
-// fused kernel applies, it is used and *fused describes the partial table it left in
-// h->d_partial_f, otherwise fused->G stays 0 and the caller runs the stand-alone statistics pass.
 // Adam's scalars as sgp_step_adam hands them over (NULL: SGD / Nesterov).
 struct AdamArgs {
     float *v2;
@@ -532,6 +613,11 @@ struct AdamArgs {
     int64_t t;
 };
 
+// One iteration; with fused != NULL the caller wants the statistics of z^(k+1) as well: when the
+// fused kernel applies, it is used and *fused describes the partial table it left, otherwise
+// fused->G stays 0 and the caller runs the stand-alone statistics pass.
+// Order: every check, then every allocation, then the launches, then (only when the launches were
+// accepted) the bookkeeping of overlap mode: a call that fails has not touched x, u, w, z.
 static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
                      float gamma, float momentum, int64_t k, void *stream, FusedStats *fused,
                      const AdamArgs *adam = nullptr)
@@ -562,19 +648,21 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     const bool complete = h->topology == SGP_TOPO_COMPLETE;
     const bool custom = h->topology == SGP_TOPO_CUSTOM;
     if (custom && h->cS == 0) return SGP_ERR_SEQUENCE;         // sgp_set_mixing has not been called
-    const bool gather = custom || (h->delay == 0 && !complete && s.distinct > 1);
-    if (gather && n > 256) return SGP_ERR_UNSUPPORTED;
-
-    int rc = ensure_device(h);
-    if (rc != SGP_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool gather = sending && (custom || (h->delay == 0 && !complete && s.distinct > 1));
 
     bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m)) &&
                (!adam || aligned16(adam->v2)) && (!z_out || aligned16(z_out));
-    if (gather && n > 64) vec = false;   // keep the LDS stash within 64 KiB
+    if (gather && n > kGatherVecMaxNodes) vec = false;   // the private columns must fit the LDS
+    if (gather && n > SGP_MAX_NODES_GATHER) return SGP_ERR_UNSUPPORTED;
     const long cols4 = vec ? (long)(h->d / 4) : 0;             // full 128-bit groups
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
+    const bool use_fused = fused && z_out && sending && fused_stats_applies(h, gather, complete, custom, adam != nullptr, cols4 > 0, tail);
+
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    if (use_fused && ((rc = ensure_fused(h)) != SGP_OK || (rc = ensure_result_events(h)) != SGP_OK)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
 
     const bool decay = h->wd != 0.0f;
     Hyper hp{};
@@ -582,7 +670,6 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     hp.mom = momentum;
     hp.wd = h->wd;
     hp.wd_mode = !decay ? 0 : (h->wd_on_x || h->biased) ? 1 : 2;
-    hp.w_old = h->d_w_old;
     if (adam) {   // bias corrections in double, rounded once
         hp.v2 = adam->v2;
         hp.beta1 = adam->beta1;
@@ -593,92 +680,100 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         hp.bc2 = (float)(1.0 - std::pow((double)adam->beta2, (double)adam->t));
         hp.eps = adam->eps;
     }
-    StepArgs a{x, m, z_out, g, w, h->d_unit_w, n, (size_t)h->ld, s.p, hp, st};
+    // the push-sum weight update, carried out by the step kernel itself
+    WeightOp wop{};
+    wop.w = w;
+    wop.p = s.p;
+    wop.biased = (int)h->biased;
+    wop.done = h->d_done;
+    wop.hop = -1;
+    const char *kname = "";
+    StepArgs a{x, m, z_out, g, wop, n, (size_t)h->ld, s.p, hp, st, &kname};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
-    const unsigned wblock = (unsigned)((n + 63) / 64 * 64);
+    // a step is one launch over the 128-bit groups plus, for d % 4 != 0 or unaligned arrays, one over
+    // the remaining scalar columns; the last of them writes the new weights back
+    auto two_launches = [&](auto &&launch4, auto &&launch1) {
+        if (cols4 > 0) {
+            a.wop.publish = tail > 0 ? 0 : 1;
+            launch4();
+        }
+        if (tail > 0) {
+            a.wop.publish = 1;
+            launch1();
+        }
+    };
 
     hipEvent_t *tev = nullptr;
     if (h->timing) {
-        if (!h->ev_made) {
-            for (int i = 0; i < SGP_TIMING_RING; ++i) {
-                SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][0]));
-                SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][1]));
-            }
-            h->ev_made = true;
-        }
         tev = h->ev[h->ev_head % SGP_TIMING_RING];
+        SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
     }
 
     if (!sending) {
         // between two communication rounds: a local step, x <- xh, w unchanged (Alg. 2, else branch
         // of the send test), which is the one-peer walk with n cycles of length 1 and weight 1
-        hipLaunchKernelGGL(k_w_keep, dim3(1), dim3(wblock), 0, st, w, n, h->d_unit_w, (int)h->biased, h->d_w_old);
-        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
-        StepArgs al = a;
-        al.p = 1.0f;
+        a.wop.kind = kWKeep;
+        a.p = 1.0f;
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            if (cols4 > 0) launch_one_peer<4, OPT, ZOUT>(al, 0, cols4, 0, 1);
-            if (tail > 0) launch_one_peer<1, OPT, ZOUT>(al, tail0, tail, 0, 1);
+            two_launches([&] { launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, 0, 1); },
+                         [&] { launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, 0, 1); });
         });
-        h->last_k = k;
     } else if (complete) {
-        StepArgs ac = a;
-        ac.p = 1.0f / (float)n;
-        hipLaunchKernelGGL(k_w_complete, dim3(1), dim3(wblock), 0, st, w, n, ac.p, h->d_unit_w,
-                           (int)h->biased, h->d_w_old);
-        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        a.p = 1.0f / (float)n;
+        a.wop.kind = kWComplete;
+        a.wop.p = a.p;
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            if (cols4 > 0) launch_complete<4, OPT, ZOUT>(ac, 0, cols4);
-            if (tail > 0) launch_complete<1, OPT, ZOUT>(ac, tail0, tail);
+            two_launches([&] { launch_complete<4, OPT, ZOUT>(a, 0, cols4); },
+                         [&] { launch_complete<1, OPT, ZOUT>(a, tail0, tail); });
         });
     } else if (custom) {
-        hipLaunchKernelGGL(k_w_custom, dim3(1), dim3(wblock), 0, st, w, n, h->d_cidx, h->d_cw, h->cS,
-                           h->d_unit_w, (int)h->biased, h->d_w_old);
-        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        a.wop.kind = kWCustom;
+        a.wop.tab = h->d_cidx;
+        a.wop.tabw = h->d_cw;
+        a.wop.S = h->cS;
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            if (cols4 > 0) launch_gather<4, OPT, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS);
-            if (tail > 0) launch_gather<1, OPT, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS);
+            two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS); },
+                         [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS); });
         });
     } else if (h->delay == 0) {
-        // w first: the fused kernel de-biases with the NEW weights and never needs the old ones
-        hipLaunchKernelGGL(k_w_mix, dim3(1), dim3(wblock), 0, st, w, n, tab_k, S, s.p, h->d_unit_w,
-                           (int)h->biased, h->d_w_old);
-        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
         if (!gather) {
             const int hop = s.distinct ? s.uniq[0] % n : 0;
             const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
             const int len = n / ncyc;
-            if (fused && !adam && z_out && n <= kStatsCache && cols4 > 0 && tail == 0) {
+            a.wop.kind = kWOnePeer;
+            a.wop.hop = s.distinct ? hop : -1;
+            if (use_fused) {
                 const unsigned Gf = grid_for(cols4, kStatsStepBlock);
-                const size_t need = (size_t)(kStatsCache + 1) * Gf;
-                if (need > h->partial_f_elems) {
-                    if (h->d_partial_f) (void)hipFree(h->d_partial_f);
-                    h->d_partial_f = nullptr;
-                    h->partial_f_elems = 0;
-                    hipError_t e = hipMalloc(&h->d_partial_f, need * sizeof(float));
-                    if (e != hipSuccess) return e == hipErrorOutOfMemory ? SGP_ERR_NOMEM : hip_fail(h, e);
-                    h->partial_f_elems = need;
-                }
+                a.wop.publish = 1;
+                a.wop.w_snap = h->d_w_snap[fused->slot];
+                float *partial = h->d_partial_f[fused->slot];
+                // the slot's event is attached to the kernel itself as its completion event (no marker of
+                // its own on the caller's stream); the reduction on the library's stream waits for it
+                hipEvent_t fin = h->ev_step[fused->slot];
                 if (opt == kOptNesterov)
-                    hipLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
-                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, hp,
-                                       h->d_partial_f);
+                    hipExtLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock),
+                                          (uint32_t)weight_lds_bytes(n), st, nullptr, fin, 0, x, m, g, z_out, a.wop, n,
+                                          (size_t)h->ld, cols4, hop, len, s.p, hp, partial);
                 else
-                    hipLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock), 0, st, x, m, g,
-                                       z_out, w, h->d_unit_w, n, (size_t)h->ld, cols4, hop, len, s.p, hp,
-                                       h->d_partial_f);
+                    hipExtLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock),
+                                          (uint32_t)weight_lds_bytes(n), st, nullptr, fin, 0, x, m, g, z_out, a.wop, n,
+                                          (size_t)h->ld, cols4, hop, len, s.p, hp, partial);
+                kname = "k_step_one_peer_stats";
                 fused->G = (int)Gf;
                 fused->hop = hop;
                 fused->len = len;
             } else
             dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-                if (cols4 > 0) launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, hop, len);
-                if (tail > 0) launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, hop, len);
+                two_launches([&] { launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, hop, len); },
+                             [&] { launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, hop, len); });
             });
         } else {
+            a.wop.kind = kWTable;
+            a.wop.tab = tab_k;
+            a.wop.S = S;
             dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-                if (cols4 > 0) launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab_k, nullptr, S);
-                if (tail > 0) launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab_k, nullptr, S);
+                two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab_k, nullptr, S); },
+                             [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab_k, nullptr, S); });
             });
         }
     } else {
@@ -694,25 +789,31 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             tab_prev = h->d_tab + (size_t)kprev * n * S;
         }
         const int cur = h->cur, prv = cur ^ 1;
-        hipLaunchKernelGGL(k_w_delay, dim3(1), dim3(wblock), 0, st, w, h->d_msgw[prv], h->d_msgw[cur],
-                           n, tab_prev, S, s.p, h->d_unit_w, (int)h->biased, h->d_w_old);
-        if (tev) SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+        a.wop.kind = kWDelay;
+        a.wop.tab = tab_prev;
+        a.wop.S = S;
+        a.wop.msgw_prev = h->d_msgw[prv];
+        a.wop.msgw_cur = h->d_msgw[cur];
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            if (cols4 > 0)
-                launch_delay<4, OPT, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb);
-            if (tail > 0)
-                launch_delay<1, OPT, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha,
-                                            hb);
+            two_launches(
+                [&] { launch_delay<4, OPT, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); },
+                [&] { launch_delay<1, OPT, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); });
         });
-        h->cur = prv;
-        h->have_msgs = true;
-        h->last_k = k;
     }
+    SGP_HIP_TRY(h, hipGetLastError());
     if (tev) {
         SGP_HIP_TRY(h, hipEventRecord(tev[1], st));
         ++h->ev_head;
     }
-    SGP_HIP_TRY(h, hipGetLastError());
+    // the launches were accepted: advance the overlap-mode sequence
+    if (h->delay) {
+        if (sending) {
+            h->cur ^= 1;
+            h->have_msgs = true;
+        }
+        h->last_k = k;
+    }
+    h->last_kernel = kname;
     return SGP_OK;
 }
 
@@ -730,25 +831,34 @@ int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const
 }
 
 // Enqueues the reduction of a partial table to the statistics and their copy into result slot
-// `slot` of the pinned host buffer.  fused == NULL: the stand-alone kernels' table [(n+1)][G];
-// else the fused kernel's.
-static int enqueue_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
-                         int slot, hipStream_t st)
+// `slot` of the pinned host buffer, and records ev_res[slot] behind the copy.
+// fused == NULL: the stand-alone kernels' table [(n+1)][G], reduced on the caller's stream.
+// Otherwise the fused step kernel's table of that slot, reduced on the library's own stream behind
+// an event, so that the caller's stream is free for the next iteration at once; the weights are then
+// taken from the copy the step kernel made (the caller's array may be overwritten by the next step
+// before the reduction has read it).
+static int enqueue_stats(sgp_handle *h, const FusedStats *fused, const float *w, int slot, hipStream_t st)
 {
     const int n = h->n;
+    int rc = ensure_result_events(h);
+    if (rc != SGP_OK) return rc;
     double *d_res = h->d_result + (size_t)slot * (8 + n);
+    hipStream_t rs = st;
     if (fused) {
-        const int B = std::min(kSlotSumBlocks, G);
-        hipLaunchKernelGGL(k_stats_slotsum, dim3(B), dim3(kSlotSumBlock), 0, st, partial, G, h->d_sums);
-        hipLaunchKernelGGL(k_stats_final_slots, dim3(1), dim3(kFinalSlotsBlock), 0, st, h->d_sums, B, n, fused->hop,
-                           fused->len, w, d_res);
+        rs = h->side;
+        SGP_HIP_TRY(h, hipStreamWaitEvent(rs, h->ev_step[slot], 0));   // recorded by the step kernel's launch
+        const int B = std::min(kSlotSumBlocks, fused->G);
+        hipLaunchKernelGGL(k_stats_reduce_slots, dim3(B), dim3(kSlotSumBlock), 0, rs, h->d_partial_f[slot], fused->G,
+                           h->d_sums_f[slot], h->d_done + kStepCounters + slot, n, fused->hop, fused->len, h->d_w_snap[slot],
+                           d_res);
     } else {
-        hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, st, partial, G, h->d_sums);
-        hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, h->d_sums, n, w, d_res);
+        hipLaunchKernelGGL(k_stats_rowsum, dim3(n + 1), dim3(kRowSumBlock), 0, rs, h->d_partial, h->G, h->d_sums);
+        hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, rs, h->d_sums, n, w, d_res);
     }
     SGP_HIP_TRY(h, hipGetLastError());
     SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result + (size_t)slot * (8 + n), d_res, (size_t)(8 + n) * sizeof(double),
-                                  hipMemcpyDeviceToHost, st));
+                                  hipMemcpyDeviceToHost, rs));
+    SGP_HIP_TRY(h, hipEventRecord(h->ev_res[slot], rs));
     return SGP_OK;
 }
 
@@ -767,16 +877,21 @@ static void read_stats(const sgp_handle *h, int slot, sgp_stats *host_out, doubl
         for (int i = 0; i < n; ++i) per_node_dist_host[i] = r[8 + i];
 }
 
-// Reduces a partial table to the statistics, copies them to the host and waits.
-static int finish_stats(sgp_handle *h, const float *partial, int G, const FusedStats *fused, const float *w,
-                        sgp_stats *host_out, double *per_node_dist_host, hipStream_t st)
+// Reduces a partial table to the statistics (slot 0), copies them to the host and waits: for the
+// result and for everything enqueued on the caller's stream before it.
+static int finish_stats(sgp_handle *h, const FusedStats *fused, const float *w, sgp_stats *host_out,
+                        double *per_node_dist_host, hipStream_t st)
 {
-    int rc = enqueue_stats(h, partial, G, fused, w, 0, st);
+    int rc = enqueue_stats(h, fused, w, 0, st);
     if (rc != SGP_OK) return rc;
+    SGP_HIP_TRY(h, hipEventSynchronize(h->ev_res[0]));
     SGP_HIP_TRY(h, hipStreamSynchronize(st));
     read_stats(h, 0, host_out, per_node_dist_host);
     return SGP_OK;
 }
+
+static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
+                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot);
 
 int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
                    float gamma, float momentum, int64_t k, sgp_stats *host_out,
@@ -787,37 +902,30 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
     int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
     if (rc != SGP_OK) return rc;
     if (fused.G > 0)
-        return finish_stats(h, h->d_partial_f, fused.G, &fused, w, host_out, per_node_dist_host,
-                            static_cast<hipStream_t>(stream));
+        return finish_stats(h, &fused, w, host_out, per_node_dist_host, static_cast<hipStream_t>(stream));
     return sgp_consensus_stats(h, z_out, w, host_out, per_node_dist_host, stream);
 }
-
-static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int mode, bool vec, const float *w,
-                     sgp_stats *host_out, double *per_node_dist_host, hipStream_t st, int slot);
 
 int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
                          float gamma, float momentum, int64_t k, void *stream)
 {
     if (!h || !z_out) return SGP_ERR_INVALID_ARG;
     if (h->pend_count >= 2) return SGP_ERR_SEQUENCE;   // fetch a result with sgp_step_stats_end first
+    int rc = ensure_result_events(h);                  // before anything is launched
+    if (rc != SGP_OK) return rc;
+    const int idx = (h->pend_head + h->pend_count) % 2;
     FusedStats fused;
-    int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
+    fused.slot = 1 + idx;
+    rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
     if (rc != SGP_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!h->ev_res_made) {
-        SGP_HIP_TRY(h, hipEventCreateWithFlags(&h->ev_res[0], hipEventDisableTiming));
-        SGP_HIP_TRY(h, hipEventCreateWithFlags(&h->ev_res[1], hipEventDisableTiming));
-        h->ev_res_made = true;
-    }
-    const int idx = (h->pend_head + h->pend_count) % 2;
     if (fused.G > 0) {
-        rc = enqueue_stats(h, h->d_partial_f, fused.G, &fused, w, 1 + idx, st);
+        rc = enqueue_stats(h, &fused, w, 1 + idx, st);
     } else {
         const bool vec = (h->ld % 4 == 0) && aligned16(z_out);
         rc = run_stats(h, z_out, StatSource{}, 0, vec, w, nullptr, nullptr, st, 1 + idx);
     }
     if (rc != SGP_OK) return rc;
-    SGP_HIP_TRY(h, hipEventRecord(h->ev_res[idx], st));
     ++h->pend_count;
     return SGP_OK;
 }
@@ -827,7 +935,7 @@ int sgp_step_stats_end(sgp_handle *h, sgp_stats *host_out, double *per_node_dist
     if (!h || !host_out) return SGP_ERR_INVALID_ARG;
     if (h->pend_count == 0) return SGP_ERR_SEQUENCE;
     const int idx = h->pend_head;
-    SGP_HIP_TRY(h, hipEventSynchronize(h->ev_res[idx]));
+    SGP_HIP_TRY(h, hipEventSynchronize(h->ev_res[1 + idx]));
     read_stats(h, 1 + idx, host_out, per_node_dist_host);
     h->pend_head = (idx + 1) % 2;
     --h->pend_count;
@@ -837,6 +945,13 @@ int sgp_step_stats_end(sgp_handle *h, sgp_stats *host_out, double *per_node_dist
 int sgp_set_kernel_timing(sgp_handle *h, int enable)
 {
     if (!h) return SGP_ERR_INVALID_ARG;
+    if (enable && !h->ev_timing_made) {   // here, not inside a step: a step allocates nothing after its first launch
+        h->ev_timing_made = true;         // release_device destroys whatever was created
+        for (int i = 0; i < SGP_TIMING_RING; ++i) {
+            SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][0]));
+            SGP_HIP_TRY(h, hipEventCreate(&h->ev[i][1]));
+        }
+    }
     h->timing = enable != 0;
     h->ev_read = h->ev_head;
     return SGP_OK;
@@ -919,8 +1034,8 @@ static int run_stats(sgp_handle *h, const float *z, const StatSource &src, int m
 {
     launch_stats_passes(h->n, h->d, h->ld, z, src, mode, vec, h->d_partial, h->G, st);
     SGP_HIP_TRY(h, hipGetLastError());
-    if (slot != 0) return enqueue_stats(h, h->d_partial, h->G, nullptr, w, slot, st);
-    return finish_stats(h, h->d_partial, h->G, nullptr, w, host_out, per_node_dist_host, st);
+    if (slot != 0) return enqueue_stats(h, nullptr, w, slot, st);
+    return finish_stats(h, nullptr, w, host_out, per_node_dist_host, st);
 }
 
 int sgp_consensus_stats(sgp_handle *h, const float *z, const float *w, sgp_stats *host_out,
@@ -954,7 +1069,6 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
     src.hp.mom = momentum;
     src.hp.wd = h->wd;
     src.hp.wd_mode = h->wd == 0.0f ? 0 : (h->wd_on_x || h->biased) ? 1 : 2;
-    src.hp.w_old = w;   // the weights handed in are the ones the coming update will replace
     const bool vec = (h->ld % 4 == 0) && aligned16(x) && aligned16(g) && (!nest || aligned16(m));
     return run_stats(h, nullptr, src, nest ? 2 : 1, vec, w, host_out, per_node_dist_host,
                      static_cast<hipStream_t>(stream), 0);

@@ -57,6 +57,12 @@ WORKLOADS = {
     "x3_n16_transformer_2peer_overlap_adam": Workload("x3_n16_transformer_2peer_overlap_adam", 16,
                                                       213_000_000, 2, 1, 1e-3, 0.0, 20, "fresh", 1e-4, 0.05,
                                                       optimizer="adam"),
+    # the two-peer blocking runs of the paper's communication-topology comparison (16 and 32 nodes,
+    # ResNet-50-sized vectors): configuration 3's / 4's shape with two out-peers and no delay
+    "x4_n32_resnet50_2peer": Workload("x4_n32_resnet50_2peer", 32, 25_557_032, 2, 0, 0.1, 0.9, 50, "fresh",
+                                      1e-3, 0.05),
+    "x5_n16_resnet50_2peer": Workload("x5_n16_resnet50_2peer", 16, 25_557_032, 2, 0, 0.1, 0.9, 50, "fresh",
+                                      1e-3, 0.05),
 }
 
 

@@ -13,7 +13,7 @@ import torch
 
 from oracle import sgp_oracle as O
 import paper_1811_10792_amd as sgp
-from paper_1811_10792_amd import synthetic as syn
+from paper_1811_10792_amd import binding, synthetic as syn
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -182,6 +182,29 @@ def test_multi_peer_gather(n, peers):
     run_both(n, 520, 520, peers, 0, min(L + 1, 5), 0.1, 0.9, seed=n + peers, w_spread=True)
 
 
+@pytest.mark.parametrize("n,d", [(150, 132), (151, 132), (600, 36)])
+def test_multi_peer_gather_at_the_node_limits(n, d):
+    """The private LDS columns of the gather kernel: 128-bit accesses up to n = 150, scalar ones up
+    to n = 600 (more than 64 KiB of LDS per block from n = 64 / n = 255 on)."""
+    run_both(n, d, d, 2, 0, 3, 0.1, 0.9, seed=n, w_spread=True)
+
+
+def test_multi_peer_gather_beyond_the_node_limit_leaves_the_state_untouched():
+    n, d = binding.SGP_MAX_NODES_GATHER + 1, 8
+    eng = sgp.SGP(n, d, peers=2)
+    x, w, u, g = (dev(a) for a in random_state(n, d, 0))
+    keep = [t.clone() for t in (x, w, u)]
+    z = torch.full_like(x, 5.0)
+    with pytest.raises(sgp.SgpError) as e:
+        eng.step(x, w, u, g, z, 0.1, 0.9, 0)
+    assert e.value.status == binding.SGP_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    for t, t0 in zip((x, w, u), keep):
+        assert torch.equal(t, t0)
+    assert bool((z == 5.0).all())
+    eng.close()
+
+
 @pytest.mark.parametrize("n,peers", [(1, 1), (2, 1), (4, 1), (16, 1), (32, 1), (5, 2), (16, 2), (33, 2),
                                      (16, 3), (12, 4)])
 def test_one_iteration_delay(n, peers):
@@ -201,12 +224,6 @@ def test_delay_sequence_and_reset():
     eng.step(x, w, u, g, None, 0.1, 0.9, 4)
     eng.reset()
     eng.step(x, w, u, g, None, 0.1, 0.9, 0)
-    eng.close()
-    eng = sgp.SGP(257, d, peers=2)
-    x, w, u, g = (dev(a) for a in random_state(257, d, 0))
-    with pytest.raises(sgp.SgpError) as e:
-        eng.step(x, w, u, g, None, 0.1, 0.9, 0)
-    assert e.value.status == -2
     eng.close()
 
 
