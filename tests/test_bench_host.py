@@ -1,6 +1,8 @@
 """Host logic of bench.py that needs no GPU: algorithmic bytes per node-parameter of every workload,
 the counter summaries it reads from profiles/, and the refusal of more than one GPU."""
+import glob
 import os
+import re
 import subprocess
 import sys
 
@@ -23,14 +25,34 @@ def test_algorithmic_bytes_per_update():
         assert bench.algorithmic_bytes_per_update(syn.WORKLOADS[name]) == b, name
 
 
+def _fields(path):
+    out = {}
+    for line in open(path):
+        m = re.match(r"^(\w+):\s*(\S+)", line)
+        if m:
+            out[m.group(1)] = m.group(2)
+    return out
+
+
 def test_committed_counter_summaries_match_the_algorithmic_traffic():
-    for name in ("c3_n16_resnet50", "c4_n32_resnet50", "c5_n16_transformer_2peer_overlap",
-                 "x2_n32_resnet50_complete"):
+    """Every committed counter summary names its kernel and shape, its traffic is the algorithmic
+    one to within 0.2 %, and bench.read_traffic hands it out only for that kernel and shape."""
+    seen = 0
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "step_kernel_*_pmc.txt"))):
+        f = _fields(path)
+        name = f["workload"]
         wl = syn.WORKLOADS[name]
-        measured = bench.read_traffic(name)
+        ld = syn.padded_ld(wl.d)
+        assert (int(f["n"]), int(f["d"]), int(f["ld"])) == (wl.n, wl.d, ld), path
+        measured, source = bench.read_traffic(name, f["kernel"], wl.n, wl.d, ld)
         algorithmic = bench.algorithmic_bytes_per_update(wl) * wl.n * wl.d
         assert measured is not None and abs(measured / algorithmic - 1.0) < 0.002, name
-    assert bench.read_traffic("no_such_workload") is None
+        assert source == os.path.join("profiles", os.path.basename(path))
+        assert bench.read_traffic(name, "k_other", wl.n, wl.d, ld) == (None, None)      # another kernel ran
+        assert bench.read_traffic(name, f["kernel"], wl.n, wl.d, ld + 256) == (None, None)
+        seen += 1
+    assert seen >= 1 and os.path.exists(os.path.join(ROOT, "profiles", "step_kernel_c4_n32_resnet50_pmc.txt"))
+    assert bench.read_traffic("no_such_workload", "k", 1, 1, 1) == (None, None)
 
 
 def test_more_than_one_gpu_is_refused_with_a_message():
