@@ -133,9 +133,30 @@ def device_normal(n: int, ld: int, std: float, seed: int, stream: int, device="c
     return out
 
 
-def sample_columns(d: int, count: int, seed: int = 0, tile: int = 1024) -> np.ndarray:
+def sample_columns(d: int, count: int, seed: int = 0, tile: int = 1024, around=(), halo: int = 512) -> np.ndarray:
     """Sorted, distinct coordinate indices for spot checks at full size: the first and last
-    `tile` coordinates (first tile and ragged tail of any launch) plus `count` random ones."""
-    edge = np.concatenate([np.arange(0, min(tile, d)), np.arange(max(0, d - tile), d)])
-    rnd = _rng(seed, 5).integers(0, d, size=count)
-    return np.unique(np.concatenate([edge, rnd])).astype(np.int64)
+    `tile` coordinates (first tile and ragged tail of any launch), `count` random ones, and the
+    `halo` coordinates before and after every coordinate listed in `around` (places where a
+    launch's work partition or the address arithmetic changes regime)."""
+    parts = [np.arange(0, min(tile, d)), np.arange(max(0, d - tile), d),
+             _rng(seed, 5).integers(0, d, size=count)]
+    for c in around:
+        parts.append(np.arange(max(0, int(c) - halo), min(d, int(c) + halo)))
+    return np.unique(np.concatenate(parts)).astype(np.int64)
+
+
+def partition_boundaries(d: int, ld: int, n: int, coords_per_block: int, parts: int = 8,
+                         byte_period: int = 1 << 31) -> list:
+    """Coordinates at which a launch over d coordinates in blocks of `coords_per_block` switches
+    from one of `parts` contiguous shares of the blocks to the next, and coordinates at which some
+    row of an [n, ld] float32 array crosses a multiple of `byte_period` bytes from the array's
+    start.  Pure index arithmetic, used to pick spot-check columns."""
+    G = (d + coords_per_block - 1) // coords_per_block
+    q, r = divmod(G, parts)
+    out = [(x * q + min(x, r)) * coords_per_block for x in range(1, parts)]
+    per = byte_period // 4
+    for i in range(n):
+        first = -(-(i * ld) // per) * per            # first multiple of the period at or after the row's start
+        for e in range(first, i * ld + d, per):
+            out.append(e - i * ld)
+    return sorted({c for c in out if 0 < c < d})

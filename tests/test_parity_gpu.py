@@ -338,7 +338,11 @@ def _full_size_spot_check(wl, steps, count=3000):
     W = torch.ones(n, dtype=torch.float32, device=DEV)
     Z = alloc.floats("z", n, ld)
     Gbuf = alloc.floats("g", n, ld)
-    cols = syn.sample_columns(d, count, wl.seed)
+    # also around the places where the launch moves from one XCD's share of the blocks to the next
+    # (256 coordinates per block in the one-peer, gather and complete kernels, 2048 in the overlap
+    # kernels) and where a row crosses a 2 GiB multiple of the array
+    around = syn.partition_boundaries(d, ld, n, 2048 if wl.delay else 256)
+    cols = syn.sample_columns(d, count, wl.seed, around=around, halo=512 if wl.delay else 128)
     cidx = torch.from_numpy(cols).to(DEV)
     xo, uo = host(X[:, cidx]), host(U[:, cidx])
     wo = np.ones(n, np.float32)
@@ -402,6 +406,63 @@ def _full_size_spot_check(wl, steps, count=3000):
     eng.close()
     del X, U, Z, G, Gbuf
     alloc.reset()
+
+
+def _full_size_every_element(wl, steps, k0=0):
+    """Consecutive iterations at full size in the benchmark's launch configuration and placement,
+    EVERY element of x, u, z (and w) compared with the float32 oracle after every iteration (the
+    oracle steps the whole state on the host: a few seconds per iteration)."""
+    n, d = wl.n, wl.d
+    ld = syn.padded_ld(d)
+    alloc = _bench_allocator()
+    X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3, out=alloc.floats("x", n, ld))
+    U = syn.device_normal(n, ld, wl.grad_std, wl.seed, 6, out=alloc.floats("u", n, ld))
+    W = torch.ones(n, dtype=torch.float32, device=DEV)
+    Z = alloc.floats("z", n, ld)
+    Gbuf = alloc.floats("g", n, ld)
+
+    def whole(T):                                    # the d used columns of every row, on the host
+        return np.ascontiguousarray(T[:, :d].cpu().numpy())
+    xo, uo, wo = whole(X), whole(U), np.ones(n, np.float32)
+    eng = sgp.SGP(n, d, ld, peers=wl.peers, delay=0)
+    for k in range(k0, k0 + steps):
+        G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + k, out=Gbuf)
+        g = whole(G)
+        if wl.stats_each_step:                       # the benchmark's call
+            s_fused = eng.step_stats(X, W, U, G, Z, wl.gamma, wl.momentum, k, per_node=True)
+        else:
+            eng.step(X, W, U, G, Z, wl.gamma, wl.momentum, k)
+        zo = O.step(O.mixing_matrix(n, wl.peers, k, np.float32), xo, wo, uo, g, wl.gamma, wl.momentum)
+        del g
+        for T, ref, what in ((X, xo, "x"), (U, uo, "u"), (Z, zo, "z")):
+            for i in range(n):                       # row by row: bounded host memory
+                got = T[i, :d].cpu().numpy()
+                if not np.array_equal(got, ref[i]):
+                    bad = np.flatnonzero(got != ref[i])
+                    raise AssertionError("%s %s k=%d node %d: %d elements differ, first at coordinate %d"
+                                         % (wl.name, what, k, i, bad.size, bad[0]))
+        same(host(W), wo, "%s w k=%d" % (wl.name, k))
+        if wl.stats_each_step and k == k0 + steps - 1:
+            dist, ref = O.consensus_stats(zo, wo)
+            assert np.abs(np.array(s_fused.per_node) - dist).max() <= 1e-5 * ref["max"]
+            assert abs(s_fused.zbar_norm - ref["zbar_norm"]) <= 1e-5 * ref["zbar_norm"]
+        del zo
+    eng.close()
+    del X, U, Z, G, Gbuf
+    alloc.reset()
+
+
+def test_full_size_config4_every_element_over_all_five_hops():
+    _full_size_every_element(syn.WORKLOADS["c4_n32_resnet50"], steps=5, k0=3)
+
+
+def test_full_size_config3_every_element_over_all_four_hops():
+    _full_size_every_element(syn.WORKLOADS["c3_n16_resnet50"], steps=4)
+
+
+def test_full_size_two_peer_blocking():
+    _full_size_spot_check(syn.WORKLOADS["x4_n32_resnet50_2peer"], steps=3)
+    _full_size_spot_check(syn.WORKLOADS["x5_n16_resnet50_2peer"], steps=2)
 
 
 def test_full_size_config3_n16_resnet50():
