@@ -24,7 +24,8 @@
  * three 96 GiB regions, and arrays that are written at the same time (x, m, z) slow each other down
  * when they share one; with x (and g), m and z in three different regions the step kernels reach
  * 80 % of the HBM peak, with back-to-back allocations 64 %.  The library takes the pointers as they
- * come; the Python package's placement module finds the regions by timing and carves the arrays.
+ * come; sgp_probe_regions (below) finds the regions of a caller's arena by timing, so that the caller
+ * can carve x, m and z out of three different ones (the Python package's placement module does that).
  * Arithmetic is IEEE binary32, round to nearest even, every
  * operation rounded separately (no fused multiply-add), correctly rounded division, subnormals
  * kept.  Sums over senders are taken in ascending sender index.
@@ -321,6 +322,38 @@ const char *sgp_last_step_kernel(const sgp_handle *h);
 #define SGP_TIMING_RING 64
 int sgp_set_kernel_timing(sgp_handle *h, int enable);
 int sgp_step_kernel_times(sgp_handle *h, float *ms_out, int32_t max, int32_t *count);
+
+/*
+ * Measurement utility: finds which parts of a caller-owned device arena interfere with each other
+ * as concurrent HBM streams.  On MI355X, arrays that are written at the same time slow each other
+ * down when they lie in the same one of (measured) three 96 GiB regions of the 288 GiB, and user
+ * space cannot see physical addresses; so nothing is assumed and the arena is classified by timing.
+ * The arena is cut into granules of granule_bytes.  A small SGP problem (32 nodes, 2^22 coordinates,
+ * one peer, Nesterov) is stepped with x, m, g inside a reference granule and z inside the granule
+ * under test; the granule belongs to the reference's region when that step is slow (above the
+ * midpoint between the fastest and the slowest candidate; less than 8 % contrast = one region).
+ * Repeats with a new reference until every granule has a class or max_classes is reached; a single
+ * granule that disagrees with two agreeing neighbours is treated as a timing outlier.
+ *   arena, arena_bytes      : device memory, 16-byte aligned; its CONTENTS ARE DESTROYED
+ *   granule_bytes           : multiple of 4096; at least 2 GiB for the probe problem to fit (smaller
+ *                             granules, or fewer than two of them, are reported as one class)
+ *   class_of_granule [arena_bytes / granule_bytes] host, out : classes numbered from 0 in order of
+ *                             first appearance; equal class = same region
+ *   probe_ms [same length]  host, out, nullable : the step-kernel time (ms) of the first pass, i.e.
+ *                             with the first granule as reference (0 where not measured)
+ *   structured              host, out : 1 if more than one region was told apart
+ * Allocates a few hundred bytes of device memory, launches a few hundred small kernels on `stream`
+ * and SYNCHRONISES it; takes of the order of a second per pass.
+ * Errors: SGP_ERR_INVALID_ARG, SGP_ERR_NOMEM, SGP_ERR_HIP.
+ */
+int sgp_probe_regions(void *arena, int64_t arena_bytes, int64_t granule_bytes, int32_t max_classes,
+                      int32_t *class_of_granule, float *probe_ms, int32_t *structured, void *stream);
+
+/* Host-only: the clean-up that sgp_probe_regions applies to its raw classes, in place: a single
+ * granule whose two neighbours agree with each other but not with it takes their class (regions are
+ * contiguous address ranges, so such a granule is a timing outlier), then the classes are renumbered
+ * from 0 in order of first appearance.  Errors: SGP_ERR_INVALID_ARG (null with count > 0, count < 0). */
+int sgp_smooth_region_classes(int32_t *class_of_granule, int32_t count);
 
 /* Measurement utility: plain 128-bit streaming copy of nbytes (multiple of 16, both pointers
  * 16-byte aligned, device memory) on `stream`.  Serves as the known-size reference when

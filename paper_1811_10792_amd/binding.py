@@ -33,7 +33,8 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_set_message_buffers", "sgp_step_stats", "sgp_set_biased", "sgp_set_topology",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
-           "sgp_consensus_stats_noalloc", "sgp_last_step_kernel")
+           "sgp_consensus_stats_noalloc", "sgp_last_step_kernel", "sgp_probe_regions",
+           "sgp_smooth_region_classes")
 
 
 class SgpError(RuntimeError):
@@ -100,6 +101,8 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_set_kernel_timing.argtypes = [vp, ctypes.c_int]
     lib.sgp_consensus_stats_noalloc.argtypes = [i32, i64, i64, vp, vp, vp, vp]
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
+    lib.sgp_probe_regions.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.POINTER(i32), vp]
+    lib.sgp_smooth_region_classes.argtypes = [vp, i32]
     lib.sgp_last_step_kernel.argtypes = [vp]
     lib.sgp_last_step_kernel.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -154,6 +157,27 @@ def sgp_consensus_stats_noalloc(n: int, d: int, ld: int, z, w, out_device, strea
     and without synchronising; layout as in include/sgp.h."""
     _check(load_library().sgp_consensus_stats_noalloc(n, d, ld, _ptr(z), _ptr(w), _ptr(out_device),
                                                       _stream(stream)), "sgp_consensus_stats_noalloc")
+
+
+def sgp_probe_regions(arena_ptr: int, arena_bytes: int, granule_bytes: int, max_classes: int = 4, stream=None):
+    """Classifies the granules of a device arena by mutual interference (see include/sgp.h).
+    Returns (classes, first_pass_ms, structured)."""
+    count = max(1, arena_bytes // granule_bytes)
+    cls = (ctypes.c_int32 * count)()
+    ms = (ctypes.c_float * count)()
+    structured = ctypes.c_int32()
+    _check(load_library().sgp_probe_regions(arena_ptr, arena_bytes, granule_bytes, max_classes,
+                                            ctypes.addressof(cls), ctypes.addressof(ms),
+                                            ctypes.byref(structured), _stream(stream)), "sgp_probe_regions")
+    return list(cls), list(ms), bool(structured.value)
+
+
+def sgp_smooth_region_classes(classes):
+    """Host-only clean-up of raw region classes (outlier granules, renumbering); returns a new list."""
+    buf = (ctypes.c_int32 * max(1, len(classes)))(*[int(c) for c in classes])
+    _check(load_library().sgp_smooth_region_classes(ctypes.addressof(buf), len(classes)),
+           "sgp_smooth_region_classes")
+    return list(buf[:len(classes)])
 
 
 class SGP:

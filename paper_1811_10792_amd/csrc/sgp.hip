@@ -27,12 +27,14 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "sgp.h"
 
@@ -1130,6 +1132,123 @@ int sgp_consensus_stats_noalloc(int32_t n, int64_t d, int64_t ld, const float *z
     hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, st, sums, n, w, out_device);
     if (hipGetLastError() != hipSuccess) return SGP_ERR_HIP;
     return SGP_OK;
+}
+
+int sgp_smooth_region_classes(int32_t *class_of_granule, int32_t count)
+{
+    if (count < 0 || (count > 0 && !class_of_granule)) return SGP_ERR_INVALID_ARG;
+    int32_t *cls = class_of_granule;
+    // regions are contiguous address ranges: a single granule whose two neighbours agree with each
+    // other but not with it is a timing outlier and takes their class
+    for (int i = 1; i + 1 < count; ++i)
+        if (cls[i - 1] == cls[i + 1] && cls[i] != cls[i - 1]) cls[i] = cls[i - 1];
+    // classes renumbered in order of first appearance
+    std::vector<int32_t> order;
+    for (int i = 0; i < count; ++i) {
+        int pos = -1;
+        for (size_t q = 0; q < order.size(); ++q)
+            if (order[q] == cls[i]) pos = (int)q;
+        if (pos < 0) {
+            order.push_back(cls[i]);
+            pos = (int)order.size() - 1;
+        }
+        cls[i] = pos;
+    }
+    return SGP_OK;
+}
+
+// Times the probe problem with its state arrays in granule `ref` and z in granule `cand`: median
+// step-kernel duration of the last four of six iterations.
+static int probe_time(sgp_handle *h, unsigned char *arena, int64_t granule, size_t arr, int ref, int cand,
+                      float *w_dev, hipStream_t st, float *ms_out)
+{
+    const int n = h->n;
+    float *x = reinterpret_cast<float *>(arena + (size_t)ref * granule);
+    float *u = reinterpret_cast<float *>(arena + (size_t)ref * granule + arr);
+    float *g = reinterpret_cast<float *>(arena + (size_t)ref * granule + 2 * arr);
+    float *z = reinterpret_cast<float *>(arena + (size_t)cand * granule + (cand == ref ? 3 * arr : 0));
+    float ones[32];
+    for (int i = 0; i < n; ++i) ones[i] = 1.0f;
+    SGP_HIP_TRY(h, hipMemsetAsync(x, 0, 3 * arr, st));
+    SGP_HIP_TRY(h, hipMemcpyAsync(w_dev, ones, (size_t)n * sizeof(float), hipMemcpyHostToDevice, st));
+    SGP_HIP_TRY(h, hipStreamSynchronize(st));      // `ones` is on this stack frame
+    for (int k = 0; k < 6; ++k) {
+        int rc = sgp_step(h, x, w_dev, u, g, z, 0.1f, 0.9f, k, st);
+        if (rc != SGP_OK) return rc;
+    }
+    float ms[8];
+    int32_t cnt = 0;
+    int rc = sgp_step_kernel_times(h, ms, 8, &cnt);
+    if (rc != SGP_OK) return rc;
+    if (cnt != 6) return SGP_ERR_HIP;
+    std::sort(ms + 2, ms + 6);
+    *ms_out = ms[4];
+    return SGP_OK;
+}
+
+int sgp_probe_regions(void *arena, int64_t arena_bytes, int64_t granule_bytes, int32_t max_classes,
+                      int32_t *class_of_granule, float *probe_ms, int32_t *structured, void *stream)
+{
+    constexpr int kProbeNodes = 32;
+    constexpr int64_t kProbeD = (int64_t)1 << 22;
+    if (!arena || !class_of_granule || !structured || granule_bytes < 4096 || (granule_bytes & 4095) ||
+        arena_bytes < granule_bytes || max_classes < 1 || !aligned16(arena))
+        return SGP_ERR_INVALID_ARG;
+    const int64_t count64 = arena_bytes / granule_bytes;
+    if (count64 > (1 << 20)) return SGP_ERR_INVALID_ARG;
+    const int count = (int)count64;
+    const size_t arr = (size_t)kProbeNodes * kProbeD * sizeof(float);
+    *structured = 0;
+    for (int i = 0; i < count; ++i) {
+        class_of_granule[i] = 0;
+        if (probe_ms) probe_ms[i] = 0.0f;
+    }
+    if (count < 2 || (int64_t)(4 * arr) > granule_bytes) return SGP_OK;   // nothing to tell apart
+
+    sgp_handle *h = nullptr;
+    int rc = sgp_create(&h, kProbeNodes, kProbeD, kProbeD, SGP_TOPO_DIRECTED_EXP, 1, 0);
+    if (rc != SGP_OK) return rc;
+    float *w_dev = nullptr;
+    std::vector<int> cls((size_t)count, -1);
+    std::vector<float> times((size_t)count, 0.0f);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char *base = static_cast<unsigned char *>(arena);
+    rc = sgp_set_kernel_timing(h, 1);
+    if (rc == SGP_OK && hipMalloc(&w_dev, kProbeNodes * sizeof(float)) != hipSuccess) rc = SGP_ERR_NOMEM;
+    for (int c = 0; c < max_classes && rc == SGP_OK; ++c) {
+        int ref = -1;
+        for (int i = 0; i < count && ref < 0; ++i)
+            if (cls[i] < 0) ref = i;
+        if (ref < 0) break;
+        float lo = 0.0f, hi = 0.0f;
+        bool first = true;
+        for (int i = 0; i < count && rc == SGP_OK; ++i) {
+            if (cls[i] >= 0) continue;
+            rc = probe_time(h, base, granule_bytes, arr, ref, i, w_dev, st, &times[i]);
+            if (c == 0 && probe_ms) probe_ms[i] = times[i];
+            lo = first ? times[i] : std::min(lo, times[i]);
+            hi = first ? times[i] : std::max(hi, times[i]);
+            first = false;
+        }
+        if (rc != SGP_OK) break;
+        if (hi < 1.08f * lo) {          // no contrast: everything left behaves like the reference
+            for (int i = 0; i < count; ++i)
+                if (cls[i] < 0) cls[i] = c;
+            break;
+        }
+        *structured = 1;
+        const float mid = 0.5f * (lo + hi);
+        for (int i = 0; i < count; ++i)
+            if (cls[i] < 0 && times[i] > mid) cls[i] = c;   // slow with the reference: same region
+        cls[ref] = c;
+    }
+    if (w_dev) (void)hipFree(w_dev);
+    (void)sgp_destroy(h);
+    if (rc != SGP_OK) return rc;
+    for (int i = 0; i < count; ++i)
+        if (cls[i] < 0) cls[i] = max_classes - 1;
+    for (int i = 0; i < count; ++i) class_of_granule[i] = cls[i];
+    return sgp_smooth_region_classes(class_of_granule, count);
 }
 
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)

@@ -1,8 +1,8 @@
 """Placement of the state arrays inside HBM (host-side plumbing, no SGP arithmetic).
 
-Measured on MI355X: the 288 GiB of HBM3E behave as three regions of 96 GiB (most likely the three
-stack-ID ranks of the 12-high stacks), and concurrent streams that live in the SAME region slow
-each other down (bank conflicts) while streams in different regions do not.  The fused step kernel
+Measured on MI355X: the 288 GiB of HBM3E behave as three regions of 96 GiB, and concurrent streams
+that live in the SAME region slow each other down while streams in different regions do not (same
+traffic and same read latency, but fewer reads in flight and more DRAM-credit stalls at the L2).  The fused step kernel
 moves 3 read and 3 write streams for each of n nodes; with x, u and z in three different regions it
 runs at 6.45 TB/s, with everything in one region at 5.2 TB/s.  A plain 1R+1W copy is hardly
 affected (6.56 vs 6.68 TB/s).
@@ -58,81 +58,14 @@ class RegionMap:
         return sum(1 for c in self.classes if c == cls) * self.granule
 
 
-def smooth_classes(classes: List[int]) -> List[int]:
-    """Regions are contiguous address ranges, so a single granule whose two neighbours agree with
-    each other but not with it is a timing outlier: it takes its neighbours' class.  Classes are then
-    renumbered in order of first appearance."""
-    out = list(classes)
-    for i in range(1, len(out) - 1):
-        if out[i - 1] == out[i + 1] != out[i]:
-            out[i] = out[i - 1]
-    order: List[int] = []
-    for c in out:
-        if c not in order:
-            order.append(c)
-    return [order.index(c) for c in out]
-
-
-def probe_regions(arena: Arena, granule: int = 8 * GIB, probe_d: int = 1 << 22, n: int = 32,
-                  max_classes: int = 4) -> RegionMap:
-    """Finds which granules of the arena interfere with each other.
-
-    A small SGP problem (n nodes, probe_d coordinates) is stepped with x, u, g inside a reference
-    granule and z inside the granule under test; a granule is in the reference's region when that
-    step is slow.  Repeats with a new reference until every granule has a class.  Destroys the
-    arena's contents.
-    """
-    from .binding import SGP
-    count = arena.nbytes // granule
-    arr = n * probe_d * 4
-    if count < 2 or 4 * arr > granule:
-        return RegionMap(granule, [0] * max(count, 1), [], False)
-    eng = SGP(n, probe_d)
-    eng.set_kernel_timing(True)
-    import torch
-    w = torch.ones(n, dtype=torch.float32, device=arena.buf.device)
-
-    def time_with(ref: int, cand: int) -> float:
-        base = ref * granule
-        x, u, g = (arena.floats(base + j * arr, n, probe_d) for j in range(3))
-        zoff = cand * granule + (3 * arr if cand == ref else 0)
-        z = arena.floats(zoff, n, probe_d)
-        for t in (x, u, g):
-            t.zero_()
-        w.fill_(1.0)
-        for k in range(6):
-            eng.step(x, w, u, g, z, 0.1, 0.9, k)
-        ms = sorted(eng.step_kernel_times()[2:])
-        return ms[len(ms) // 2]
-
-    classes = [-1] * count
-    first_times: List[float] = []
-    structured = False
-    for cls in range(max_classes):
-        todo = [i for i in range(count) if classes[i] < 0]
-        if not todo:
-            break
-        ref = todo[0]
-        times = {i: time_with(ref, i) for i in todo}
-        if cls == 0:
-            first_times = [times[i] for i in range(count)]
-        lo, hi = min(times.values()), max(times.values())
-        if hi < 1.08 * lo:
-            # no contrast: everything left behaves like the reference
-            for i in todo:
-                classes[i] = cls
-            break
-        structured = True
-        mid = 0.5 * (lo + hi)
-        for i in todo:
-            if times[i] > mid:
-                classes[i] = cls
-        classes[ref] = cls
-    for i in range(count):
-        if classes[i] < 0:
-            classes[i] = max_classes - 1
-    eng.close()
-    return RegionMap(granule, smooth_classes(classes), first_times, structured)
+def probe_regions(arena: Arena, granule: int = 8 * GIB, max_classes: int = 4) -> RegionMap:
+    """Finds which granules of the arena interfere with each other: the library's
+    sgp_probe_regions does the timing and the classification (a small SGP problem is stepped with
+    x, u, g inside a reference granule and z inside the granule under test; slow = same region).
+    Destroys the arena's contents."""
+    from .binding import sgp_probe_regions
+    classes, times, structured = sgp_probe_regions(arena.buf.data_ptr(), arena.nbytes, granule, max_classes)
+    return RegionMap(granule, classes, times, structured)
 
 
 class Placer:
@@ -234,3 +167,73 @@ class StateAllocator:
                         "region_of_granule": "".join(str(c) for c in self.regions.classes),
                         "structured": self.regions.structured, "arrays": dict(self.placed)})
         return out
+
+
+def _report() -> None:
+    """Measurement report behind the region-aware placement (python -m paper_1811_10792_amd.placement):
+    the probe's map, the step time of the benchmark's problem as a function of where z lies, the
+    step and the plain copy with the arrays in one region and in different ones."""
+    import torch
+    from .binding import SGP, sgp_copy
+    from . import synthetic as syn
+    torch.cuda.set_device(0)
+    placer, regions = make_placer()
+    if placer is None:
+        print("no arena could be allocated")
+        return
+    arena, g = placer.arena, regions.granule
+    print("arena %d GiB, granule %d GiB, structured %s" % (arena.nbytes // GIB, g // GIB, regions.structured))
+    print("region of each granule: " + "".join(str(c) for c in regions.classes))
+    print("probe (n = 32, d = 2^22; x, u, g in granule 0, z in granule i), step-kernel ms per granule i:")
+    print("  " + " ".join("%.3f" % t for t in regions.times_ms))
+    n, d = 32, 25_557_032
+    ld = syn.padded_ld(d)
+    arr = n * ld * 4
+    w = torch.ones(n, dtype=torch.float32, device="cuda")
+    eng = SGP(n, d, ld)
+    eng.set_kernel_timing(True)
+
+    def step_ms(offs):
+        x, u, gr, z = (arena.floats(o, n, ld) for o in offs)
+        for t in (x, u, gr):
+            t.zero_()
+        w.fill_(1.0)
+        for k in range(7):
+            eng.step(x, w, u, gr, z, 0.1, 0.9, k)
+        ms = sorted(eng.step_kernel_times()[2:])
+        return ms[len(ms) // 2]
+
+    def up(nbytes):
+        return (nbytes + 4095) // 4096 * 4096
+    a = up(arr)
+    count = arena.nbytes // g
+    print("benchmark problem (n = 32, d = 25,557,032, 3.27 GB per array): x, u, g at the start of granules 0-1, "
+          "z at the start of granule i; step-kernel ms:")
+    row = []
+    for i in range(2, count - 1):
+        row.append("%d:%.3f" % (i, step_ms((0, a, 2 * a, i * g))))
+    print("  " + " ".join(row))
+    runs = {c: max(regions.runs(c), key=lambda r: r[1]) for c in set(regions.classes)}
+    if len(runs) >= 3:
+        r0, r1, r2 = (runs[c][0] + 1 for c in (0, 1, 2))
+        print("all four arrays in region 0:                    %.3f ms" % step_ms((r0 * g, r0 * g + a, r0 * g + 2 * a, r0 * g + 3 * a)))
+        print("x, g in region 0, u in region 1, z in region 2: %.3f ms" % step_ms((r0 * g, r1 * g, r0 * g + a, r2 * g)))
+        print("x, g, u in region 0, z in region 1:             %.3f ms" % step_ms((r0 * g, r0 * g + a, r0 * g + 2 * a, r1 * g)))
+        s0, s1, d1 = arena.floats(r0 * g, n, ld), arena.floats(r0 * g + a, n, ld), arena.floats(r1 * g, n, ld)
+        for name, dst in (("inside region 0", s1), ("region 0 -> region 1", d1)):
+            for _ in range(3):
+                sgp_copy(dst, s0)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                sgp_copy(dst, s0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            print("plain copy of 3.27 GB %-22s %.3f ms = %.2f TB/s" % (name + ":", ms, 2 * arr / ms / 1e9))
+    eng.close()
+
+
+if __name__ == "__main__":
+    _report()

@@ -74,7 +74,7 @@ def test_single_class_map_still_carves_sequentially():
 
 
 def test_smoothing_removes_isolated_outliers_and_renumbers():
-    from paper_1811_10792_amd.placement import smooth_classes
+    from paper_1811_10792_amd.binding import sgp_smooth_region_classes as smooth_classes
     raw = [0] * 12 + [1] * 4 + [2] + [1] * 7 + [3] * 11
     assert smooth_classes(raw) == [0] * 12 + [1] * 12 + [2] * 11
     assert smooth_classes([0, 0, 1, 1]) == [0, 0, 1, 1]          # a real boundary stays
