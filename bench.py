@@ -39,6 +39,10 @@ def algorithmic_bytes_per_update(wl) -> float:
     total = float(reads + writes)
     if wl.delay:                                  # previous messages read, new messages written,
         total += 8.0 / wl.delay                   # at one iteration in every tau
+    if wl.storage != "f32":                       # storage experiment: g and z held as bfloat16,
+        total -= 4.0                              # 2 bytes less for each
+        if wl.storage == "bf16_guz":              # and the momentum: 2 less read, 2 less written
+            total -= 4.0
     return total
 
 
@@ -187,13 +191,28 @@ def main():
     complete = wl.topology == "complete"
     eng = sgp.SGP(n, d, ld, topology=1 if complete else 0, peers=wl.peers, delay=wl.delay)
     X = syn.device_normal(n, ld, wl.x_std, wl.seed, 3, out=alloc.floats("x", n, ld))
-    U = alloc.floats("u", n, ld).zero_()
     W = torch.ones(n, dtype=torch.float32, device="cuda")
-    Z = alloc.floats("z", n, ld)
     adam = wl.optimizer == "adam"
     V2 = alloc.floats("v", n, ld).zero_() if adam else None
-    pool = [syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i, out=alloc.floats("g", n, ld, "g%d" % i))
-            for i in range(max(1, args.pool))]
+    h16 = wl.storage != "f32"                     # storage experiment: some arrays held as bfloat16
+    storage = {"f32": 0, "bf16_gz": sgp.binding.SGP_STORE_BF16_GZ,
+               "bf16_guz": sgp.binding.SGP_STORE_BF16_GZ | sgp.binding.SGP_STORE_BF16_U}[wl.storage]
+
+    def halves(role, name=None):                  # [n, ld] bfloat16 carved like a float array of half the width
+        return alloc.floats(role, n, ld // 2, name).view(torch.bfloat16)
+    if wl.storage == "bf16_guz":
+        U = halves("u").zero_()
+    else:
+        U = alloc.floats("u", n, ld).zero_()
+    Z = halves("z") if h16 else alloc.floats("z", n, ld)
+    pool = []
+    for i in range(max(1, args.pool)):
+        if h16:
+            G = halves("g", "g%d" % i)
+            G.copy_(syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i))
+        else:
+            G = syn.device_normal(n, ld, wl.grad_std, wl.seed, 100 + i, out=alloc.floats("g", n, ld, "g%d" % i))
+        pool.append(G)
     if wl.delay:
         eng.set_message_buffers(alloc.floats("msg0", n, ld), alloc.floats("msg1", n, ld))
     do_stats = wl.stats_each_step and not args.no_stats
@@ -224,6 +243,9 @@ def main():
         if adam:
             eng.step_adam(X, W, U, V2, pool[k % len(pool)], Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
             return eng.consensus_stats(Z, W) if do_stats else None
+        if h16:
+            eng.step_bf16(X, W, U, pool[k % len(pool)], Z, wl.gamma, wl.momentum, k, storage)
+            return None
         if do_stats and not args.separate_stats:    # one call: statistics fused into the step kernel
             return eng.step_stats(X, W, U if nest else None, pool[k % len(pool)], Z, wl.gamma,
                                   wl.momentum, k)
@@ -268,7 +290,7 @@ def main():
         last = one_step(k)
         k += 1
     if args.calibrate_copy:
-        sgp.sgp_copy(Z, pool[0])          # n*ld*4 bytes read, n*ld*4 bytes written
+        sgp.sgp_copy(X, X.clone() if h16 else pool[0]) if h16 else sgp.sgp_copy(Z, pool[0])   # n*ld*4 bytes read and written
     torch.cuda.synchronize()
 
     # ---- the timed region: exactly --steps steps, nothing but the steps ------------------------
@@ -312,7 +334,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if not h16 else "f32 arithmetic, bfloat16 storage of %s" % ("g, z, u" if wl.storage == "bf16_guz" else "g, z"),
+        "data": "synthetic",
         "config": {"workload": wl.name, "n": n, "d": d, "ld": ld, "topology": wl.topology,
                    "peers": wl.peers, "delay": wl.delay,
                    "optimizer": wl.optimizer, "momentum": wl.momentum, "gamma": wl.gamma,
@@ -343,7 +366,7 @@ def main():
     eng.close()
     del X, U, Z, V2, pool, alloc
     torch.cuda.empty_cache()
-    if args.placement == "regions" and not args.no_default_placement:
+    if args.placement == "regions" and not args.no_default_placement and not h16:
         out["default_placement"] = default_placement_leg(wl, ld, args, bpu)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -205,6 +205,25 @@ int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float 
 int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const float *g, float *z_out,
                   float gamma, float beta1, float beta2, float eps, int64_t t, int64_t k, void *stream);
 
+/*
+ * Bandwidth experiment, NOT part of the paper's method: sgp_step with some arrays stored as bfloat16
+ * (the upper 16 bits of a binary32: 8 exponent bits, 7 fraction bits).  Arithmetic is unchanged
+ * (binary32, operation by operation as in sgp_step); a stored value is widened exactly when it is
+ * loaded and rounded to nearest, ties to even, when it is stored (NaN stays NaN).  In particular the
+ * local step uses the new momentum as computed, not as stored.
+ *   storage = SGP_STORE_BF16_GZ                    : g and z_out are bfloat16 [n][ld]; 20 bytes of HBM
+ *                                                    traffic per node-parameter instead of 24
+ *   storage = SGP_STORE_BF16_GZ | SGP_STORE_BF16_U : m is bfloat16 [n][ld] as well; 16 bytes
+ * x [n][ld] and w [n] stay float.  Blocking mode (delay 0) on the exponential graph with one
+ * distinct out-peer and momentum != 0 only: anything else is SGP_ERR_UNSUPPORTED.  The fast path
+ * needs ld % 4 == 0, 16-byte aligned float arrays and 8-byte aligned bfloat16 arrays.
+ * Other arguments, errors and weight handling as for sgp_step.
+ */
+#define SGP_STORE_BF16_GZ 1
+#define SGP_STORE_BF16_U 2
+int sgp_step_bf16(sgp_handle *h, float *x, float *w, void *m, const void *g16, void *z16, float gamma,
+                  float momentum, int64_t k, int32_t storage, void *stream);
+
 /* z_i = x_i / w_i for all nodes (last line of Alg. 1); x [n][ld], w [n], z [n][ld] device.
  * Used for z^(0) and whenever sgp_step was called with z_out == NULL. */
 int sgp_debias(sgp_handle *h, const float *x, const float *w, float *z, void *stream);

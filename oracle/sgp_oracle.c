@@ -17,6 +17,9 @@
  *   sgpo_debias_*          z = x / w
  *   sgpo_consensus_stats   distance of every node's de-biased parameters to the node-wise
  *                          average (the "parameter deviations" paragraph and figure)
+ *   sgpo_step_bf16         (not in the paper: storage experiment) sgpo_step_f32 with g, z and
+ *                          optionally u held in memory as bfloat16; pinned by reduction to
+ *                          sgpo_step_f32 on the widened inputs and to torch's bfloat16 rounding
  *
  * Pins (tests/test_oracle_pins.py): printed 4-node mixing matrix and its four update equations,
  * printed 8-node neighbour list, exact averaging after one cycle for n = 32 in 5 iterations,
@@ -113,4 +116,79 @@ void sgpo_consensus_stats(int n, int64_t d, const double *z, const double *w, do
     out[3] = wsum;
     out[4] = sqrt(zn);
     free(zbar);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Storage experiment (not part of the paper's method): the binary32 iteration of sgpo_step_f32
+ * with some arrays held in memory as bfloat16, i.e. the upper 16 bits of a binary32 (1 sign, 8
+ * exponent, 7 fraction bits).  Loading widens exactly (append 16 zero bits).  Storing rounds to
+ * the nearest bfloat16, ties to the one with an even last bit; a value beyond the largest finite
+ * bfloat16 by half a step or more becomes infinity; NaN stays NaN.
+ * ------------------------------------------------------------------------------------------ */
+float sgpo_bf16_to_float(uint16_t h)
+{
+    uint32_t b = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &b, sizeof f);
+    return f;
+}
+
+uint16_t sgpo_float_to_bf16(float f)
+{
+    uint32_t b;
+    memcpy(&b, &f, sizeof b);
+    uint32_t keep = b >> 16, drop = b & 0xffffu;
+    if ((b & 0x7f800000u) == 0x7f800000u && (b & 0x007fffffu) != 0u) return (uint16_t)(keep | 0x0040u);
+    if (drop > 0x8000u || (drop == 0x8000u && (keep & 1u))) keep += 1u;   /* a carry runs into the exponent */
+    return (uint16_t)keep;
+}
+
+/*
+ * One SGP iteration (Alg. 3, Nesterov momentum) with g given and z returned as bfloat16, and the
+ * momentum buffer held as bfloat16 when u_is_bf16 != 0 (then u points to uint16_t [n][d], else to
+ * float [n][d]).  Everything between load and store is sgpo_step_f32's arithmetic: the local step
+ * uses the new momentum as computed, the stored copy is its rounding.
+ */
+int sgpo_step_bf16(int n, int64_t d, const float *P, float *x, float *w, void *u, const uint16_t *g16,
+                   uint16_t *z16, float gamma, float m, int u_is_bf16)
+{
+    float *w_new = (float *)malloc(sizeof(float) * (size_t)n);
+    if (!w_new) return -1;
+    for (int i = 0; i < n; i++) {
+        float acc = 0.0f;
+        for (int j = 0; j < n; j++) {
+            float term = P[(size_t)i * n + j] * w[j];
+            acc = acc + term;
+        }
+        w_new[i] = acc;
+    }
+#pragma omp parallel
+    {
+        float *xh = (float *)malloc(sizeof(float) * (size_t)n);
+#pragma omp for schedule(static)
+        for (int64_t e = 0; e < d; e++) {
+            for (int i = 0; i < n; i++) {
+                size_t a = (size_t)i * (size_t)d + (size_t)e;
+                float ui = u_is_bf16 ? sgpo_bf16_to_float(((uint16_t *)u)[a]) : ((float *)u)[a];
+                float gi = sgpo_bf16_to_float(g16[a]);
+                xh[i] = sgpo_local_step_f32(x[a], 0.0f, &ui, NULL, gi, gamma, m, 1, 0.0f, NULL);
+                if (u_is_bf16) ((uint16_t *)u)[a] = sgpo_float_to_bf16(ui);
+                else ((float *)u)[a] = ui;
+            }
+            for (int i = 0; i < n; i++) {
+                float acc = 0.0f;
+                for (int j = 0; j < n; j++) {
+                    float term = P[(size_t)i * n + j] * xh[j];
+                    acc = acc + term;
+                }
+                size_t a = (size_t)i * (size_t)d + (size_t)e;
+                x[a] = acc;
+                z16[a] = sgpo_float_to_bf16(acc / w_new[i]);
+            }
+        }
+        free(xh);
+    }
+    for (int i = 0; i < n; i++) w[i] = w_new[i];
+    free(w_new);
+    return 0;
 }

@@ -62,6 +62,12 @@ def _load():
                 f = getattr(lib, "sgpo_debias" + sfx)
                 f.argtypes = [i32, i64, vp, vp, vp]
                 f.restype = None
+            lib.sgpo_step_bf16.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, i32]
+            lib.sgpo_step_bf16.restype = i32
+            lib.sgpo_float_to_bf16.argtypes = [ctypes.c_float]
+            lib.sgpo_float_to_bf16.restype = ctypes.c_uint16
+            lib.sgpo_bf16_to_float.argtypes = [ctypes.c_uint16]
+            lib.sgpo_bf16_to_float.restype = ctypes.c_float
             lib.sgpo_consensus_stats.argtypes = [i32, i64, vp, vp, vp, vp]
             lib.sgpo_consensus_stats.restype = None
             lib.sgpo_set_threads.argtypes = [i32]
@@ -221,3 +227,27 @@ def consensus_stats(z, w):
                                  out.ctypes.data)
     return dist, {"max": out[0], "mean": out[1], "min": out[2], "w_sum": out[3],
                   "zbar_norm": out[4]}
+
+
+def float_to_bf16(f: float) -> int:
+    """Bit pattern of the bfloat16 nearest to the binary32 value f (ties to even)."""
+    return int(_load().sgpo_float_to_bf16(float(np.float32(f))))
+
+
+def bf16_to_float(h: int) -> float:
+    return float(_load().sgpo_bf16_to_float(int(h)))
+
+
+def step_bf16(P, x, w, u, g16, gamma, m):
+    """Storage experiment: one Nesterov iteration with g16 (uint16 bit patterns of bfloat16) as the
+    gradient; u is float32 or uint16 (bfloat16 storage of the momentum).  Updates x, w, u in place and
+    returns z as uint16 bit patterns."""
+    n, d = x.shape
+    z16 = np.empty((n, d), dtype=np.uint16)
+    u_is_bf16 = u.dtype == np.uint16
+    rc = _load().sgpo_step_bf16(n, d, _chk(P, np.float32, (n, n)), _chk(x, np.float32, (n, d)),
+                                _chk(w, np.float32, (n,)), _chk(u, np.uint16 if u_is_bf16 else np.float32, (n, d)),
+                                _chk(g16, np.uint16, (n, d)), z16.ctypes.data, float(gamma), float(m), int(u_is_bf16))
+    if rc != 0:
+        raise MemoryError("oracle step failed")
+    return z16

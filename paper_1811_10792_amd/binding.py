@@ -25,6 +25,8 @@ SGP_TOPO_DIRECTED_EXP = 0
 SGP_TOPO_COMPLETE = 1
 SGP_TOPO_CUSTOM = 2
 SGP_MAX_NODES_GATHER = 600
+SGP_STORE_BF16_GZ = 1
+SGP_STORE_BF16_U = 2
 
 # every symbol include/sgp.h declares
 EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
@@ -34,7 +36,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
            "sgp_consensus_stats_noalloc", "sgp_last_step_kernel", "sgp_probe_regions",
-           "sgp_smooth_region_classes")
+           "sgp_smooth_region_classes", "sgp_step_bf16")
 
 
 class SgpError(RuntimeError):
@@ -103,6 +105,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     lib.sgp_probe_regions.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.POINTER(i32), vp]
     lib.sgp_smooth_region_classes.argtypes = [vp, i32]
+    lib.sgp_step_bf16.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, i32, vp]
     lib.sgp_last_step_kernel.argtypes = [vp]
     lib.sgp_last_step_kernel.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -228,6 +231,20 @@ class SGP:
         self._expect(w, "w", rows_only=True)
         _check(self._lib.sgp_step_adam(self._h, _ptr(x), _ptr(w), _ptr(m1), _ptr(m2), _ptr(g), _ptr(z_out),
                                        gamma, beta1, beta2, eps, t, k, _stream(stream)), "sgp_step_adam")
+
+    def step_bf16(self, x, w, m, g16, z16, gamma: float, momentum: float, k: int, storage: int,
+                  stream=None) -> None:
+        """Bandwidth experiment: one iteration with g and z (and, with SGP_STORE_BF16_U, m) held as
+        bfloat16 tensors of shape [n, ld]; x and w stay float32."""
+        import torch
+        self._expect(x, "x")
+        self._expect(w, "w", rows_only=True)
+        for t, name, half in ((g16, "g16", True), (z16, "z16", True), (m, "m", bool(storage & SGP_STORE_BF16_U))):
+            want = torch.bfloat16 if half else torch.float32
+            if not t.is_cuda or t.dtype != want or not t.is_contiguous() or t.numel() != self.n * self.ld:
+                raise ValueError("%s must be a contiguous %s CUDA tensor of %d elements" % (name, want, self.n * self.ld))
+        _check(self._lib.sgp_step_bf16(self._h, _ptr(x), _ptr(w), _ptr(m), _ptr(g16), _ptr(z16), gamma, momentum,
+                                       k, storage, _stream(stream)), "sgp_step_bf16")
 
     def step_stats(self, x, w, m, g, z_out, gamma: float, momentum: float, k: int,
                    per_node: bool = False, stream=None) -> Stats:

@@ -832,6 +832,74 @@ int sgp_step_adam(sgp_handle *h, float *x, float *w, float *m1, float *m2, const
     return step_impl(h, x, w, m1, g, z_out, gamma, 0.0f, k, stream, nullptr, &adam);
 }
 
+int sgp_step_bf16(sgp_handle *h, float *x, float *w, void *m, const void *g16, void *z16, float gamma,
+                  float momentum, int64_t k, int32_t storage, void *stream)
+{
+    if (!h || !x || !w || !m || !g16 || !z16 || k < 0) return SGP_ERR_INVALID_ARG;
+    if (storage != SGP_STORE_BF16_GZ && storage != (SGP_STORE_BF16_GZ | SGP_STORE_BF16_U)) return SGP_ERR_INVALID_ARG;
+    if (z16 == g16 || z16 == m || g16 == m || (void *)x == m) return SGP_ERR_INVALID_ARG;
+    const bool u16 = (storage & SGP_STORE_BF16_U) != 0;
+    auto aligned2 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 1u) == 0; };
+    if (!aligned4(x) || !aligned4(w) || !aligned2(g16) || !aligned2(z16) || !(u16 ? aligned2(m) : aligned4(m)))
+        return SGP_ERR_ALIGNMENT;
+    const int n = h->n;
+    const Schedule s = make_schedule(n, h->peers, k);
+    // the experiment covers the blocking one-peer step with Nesterov momentum (Alg. 3)
+    if (h->delay != 0 || h->topology != SGP_TOPO_DIRECTED_EXP || s.distinct > 1 || momentum == 0.0f)
+        return SGP_ERR_UNSUPPORTED;
+    int rc = ensure_device(h);
+    if (rc != SGP_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    auto aligned8 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0; };
+    const bool vec = (h->ld % 4 == 0) && aligned16(x) && (u16 ? aligned8(m) : aligned16(m)) && aligned8(g16) &&
+                     aligned8(z16);
+    const long cols4 = vec ? (long)(h->d / 4) : 0;      // groups of four coordinates
+    const size_t tail0 = (size_t)cols4 * 4;
+    const long tail = (long)(h->d - (int64_t)tail0);    // scalar columns after them
+    Hyper hp{};
+    hp.gamma = gamma;
+    hp.mom = momentum;
+    hp.wd = h->wd;
+    hp.wd_mode = h->wd == 0.0f ? 0 : (h->wd_on_x || h->biased) ? 1 : 2;
+    const int hop = s.distinct ? s.uniq[0] % n : 0;
+    const int len = s.distinct ? n / gcd_int(n, hop) : 1;
+    WeightOp wop{};
+    wop.w = w;
+    wop.kind = kWOnePeer;
+    wop.hop = s.distinct ? hop : -1;
+    wop.p = s.p;
+    wop.biased = (int)h->biased;
+    wop.done = h->d_done;
+
+    hipEvent_t *tev = nullptr;
+    if (h->timing) {
+        tev = h->ev[h->ev_head % SGP_TIMING_RING];
+        SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
+    }
+    auto launch = [&](auto kernel, int cols_per_item, size_t col0, long ncols, int publish) {
+        wop.publish = publish;
+        hipLaunchKernelGGL(kernel, dim3(grid_for(ncols, kOpBlock * cols_per_item)), dim3(kOpBlock),
+                           weight_lds_bytes(n), st, x, m, g16, z16, wop, n, (size_t)h->ld, col0, ncols, hop, len,
+                           s.p, hp);
+    };
+    if (cols4 > 0) {
+        if (u16) launch(k_step_one_peer_h16<4, 3>, kH16Cols, 0, cols4, tail > 0 ? 0 : 1);
+        else launch(k_step_one_peer_h16<4, 1>, kH16Cols, 0, cols4, tail > 0 ? 0 : 1);
+    }
+    if (tail > 0) {
+        if (u16) launch(k_step_one_peer_h16<1, 3>, kH16Cols, tail0, tail, 1);
+        else launch(k_step_one_peer_h16<1, 1>, kH16Cols, tail0, tail, 1);
+    }
+    SGP_HIP_TRY(h, hipGetLastError());
+    if (tev) {
+        SGP_HIP_TRY(h, hipEventRecord(tev[1], st));
+        ++h->ev_head;
+    }
+    h->last_kernel = "k_step_one_peer_h16";
+    return SGP_OK;
+}
+
 // Enqueues the reduction of a partial table to the statistics and their copy into result slot
 // `slot` of the pinned host buffer, and records ev_res[slot] behind the copy.
 // fused == NULL: the stand-alone kernels' table [(n+1)][G], reduced on the caller's stream.

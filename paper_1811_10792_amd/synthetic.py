@@ -33,6 +33,8 @@ class Workload:
     seed: int = 0
     optimizer: str = "nesterov"   # "nesterov" (momentum 0: plain SGD) or "adam" (beta 0.9 / 0.98, eps 1e-8)
     topology: str = "exp"  # "exp": directed exponential graph; "complete": every entry of P is 1/n
+    storage: str = "f32"   # "f32", or the 16-bit storage experiment: "bf16_gz" (g and z held as
+                           # bfloat16) / "bf16_guz" (the momentum as well); arithmetic is float32 always
 
 
 # The five configurations of the build's baseline description, in its order, then extensions.
@@ -63,6 +65,12 @@ WORKLOADS = {
                                       1e-3, 0.05),
     "x5_n16_resnet50_2peer": Workload("x5_n16_resnet50_2peer", 16, 25_557_032, 2, 0, 0.1, 0.9, 50, "fresh",
                                       1e-3, 0.05),
+    # storage experiment, not in the paper: configuration 4's shape (without the statistics) with g
+    # and z, then also the momentum, held in memory as bfloat16; 20 and 16 bytes per node-parameter
+    "h1_n32_resnet50_bf16_gz": Workload("h1_n32_resnet50_bf16_gz", 32, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
+                                        1e-3, 0.05, storage="bf16_gz"),
+    "h2_n32_resnet50_bf16_guz": Workload("h2_n32_resnet50_bf16_guz", 32, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
+                                         1e-3, 0.05, storage="bf16_guz"),
 }
 
 

@@ -26,7 +26,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "sgp.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(sgp_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(sgp_[a-z0-9_]+)\s*\(", header))
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
