@@ -88,6 +88,7 @@ constexpr int kStatsCache = 32;   // nodes whose z the small-n statistics kernel
 namespace {
 constexpr int kStatsGridMax = 2048;
 constexpr int kResultSlots = 3;   // statistics results: one synchronous, two in flight
+constexpr size_t kCachedStateBytes = (size_t)160 << 20;   // x, u, g, z together: below this, cached accesses
 constexpr int kStepCounters = (1 + kCountLines) * kCountStride;   // the step kernels' counters of finished blocks
 }  // namespace
 
@@ -309,15 +310,20 @@ struct StepArgs {
     Hyper hp;
     hipStream_t stream;
     const char **name;    // receives the name of the kernel launched
+    bool cached;          // small problem: ordinary loads and stores instead of streaming ones
 };
 
 template <int V, int OPT, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
-    hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
-                       dim3(kOpBlock), weight_lds_bytes(a.n),
-                       a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols, h,
-                       len, a.p, a.hp);
+    if (a.cached)
+        hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT, true>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
+                           dim3(kOpBlock), weight_lds_bytes(a.n), a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld,
+                           col0, ncols, h, len, a.p, a.hp);
+    else
+        hipLaunchKernelGGL((k_step_one_peer<V, OPT, ZOUT, false>), dim3(grid_for(ncols, kOpBlock * kOpCols)),
+                           dim3(kOpBlock), weight_lds_bytes(a.n), a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld,
+                           col0, ncols, h, len, a.p, a.hp);
     *a.name = "k_step_one_peer";
 }
 
@@ -690,7 +696,10 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     wop.done = h->d_done;
     wop.hop = -1;
     const char *kname = "";
-    StepArgs a{x, m, z_out, g, wop, n, (size_t)h->ld, s.p, hp, st, &kname};
+    // a problem whose arrays (x, u, g, z) all stay in the 256 MB last-level cache from one iteration to
+    // the next is better served by ordinary loads and stores than by streaming ones
+    const bool cached = (size_t)n * (size_t)h->ld * sizeof(float) * 4 <= kCachedStateBytes;
+    StepArgs a{x, m, z_out, g, wop, n, (size_t)h->ld, s.p, hp, st, &kname, cached};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     // a step is one launch over the 128-bit groups plus, for d % 4 != 0 or unaligned arrays, one over
     // the remaining scalar columns; the last of them writes the new weights back
@@ -752,14 +761,18 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
                 // the slot's event is attached to the kernel itself as its completion event (no marker of
                 // its own on the caller's stream); the reduction on the library's stream waits for it
                 hipEvent_t fin = h->ev_step[fused->slot];
-                if (opt == kOptNesterov)
-                    hipExtLaunchKernelGGL(k_step_one_peer_stats<true>, dim3(Gf), dim3(kStatsStepBlock),
-                                          (uint32_t)weight_lds_bytes(n), st, nullptr, fin, 0, x, m, g, z_out, a.wop, n,
-                                          (size_t)h->ld, cols4, hop, len, s.p, hp, partial);
-                else
-                    hipExtLaunchKernelGGL(k_step_one_peer_stats<false>, dim3(Gf), dim3(kStatsStepBlock),
-                                          (uint32_t)weight_lds_bytes(n), st, nullptr, fin, 0, x, m, g, z_out, a.wop, n,
-                                          (size_t)h->ld, cols4, hop, len, s.p, hp, partial);
+                auto go = [&](auto kernel) {
+                    hipExtLaunchKernelGGL(kernel, dim3(Gf), dim3(kStatsStepBlock), (uint32_t)weight_lds_bytes(n), st,
+                                          nullptr, fin, 0, x, m, g, z_out, a.wop, n, (size_t)h->ld, cols4, hop, len,
+                                          s.p, hp, partial);
+                };
+                if (opt == kOptNesterov) {
+                    if (cached) go(k_step_one_peer_stats<true, true>);
+                    else go(k_step_one_peer_stats<true, false>);
+                } else {
+                    if (cached) go(k_step_one_peer_stats<false, true>);
+                    else go(k_step_one_peer_stats<false, false>);
+                }
                 kname = "k_step_one_peer_stats";
                 fused->G = (int)Gf;
                 fused->hop = hop;
