@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--pool", type=int, default=2, help="pre-drawn gradient buffers to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stats", action="store_true", help="skip the per-step consensus statistics")
+    ap.add_argument("--stats", action="store_true",
+                    help="take the consensus statistics in every step also for a workload that does not ask for them")
     ap.add_argument("--sync-stats", action="store_true",
                     help="fetch the statistics of every step before launching the next one (sgp_step_stats) "
                          "instead of one step late (sgp_step_stats_begin / _end)")
@@ -215,7 +217,7 @@ def main():
         pool.append(G)
     if wl.delay:
         eng.set_message_buffers(alloc.floats("msg0", n, ld), alloc.floats("msg1", n, ld))
-    do_stats = wl.stats_each_step and not args.no_stats
+    do_stats = (wl.stats_each_step or args.stats) and not args.no_stats and not h16
     stream = torch.cuda.current_stream()
 
     k = 0

@@ -254,11 +254,15 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
 /*
  * sgp_step followed by sgp_consensus_stats of the z^(k+1) it wrote, in one call (Alg. 1 / Alg. 3
  * plus the "Parameter deviations" statistics).  Arguments as in those two calls; z_out and
- * host_out are required.  For one out-peer without delay, n <= 32, d % 4 == 0 and the 128-bit
- * layout, the statistics are accumulated inside the step kernel while z is still in registers
- * (z is not read back from HBM); otherwise the two kernels run one after the other.  The state
- * written is identical to sgp_step's; the statistics agree with sgp_consensus_stats to rounding
- * (a different reference row is subtracted before squaring).  SYNCHRONISES the stream.
+ * host_out are required.  With n <= 32, d % 4 == 0, the 128-bit layout and SGD or Nesterov as the
+ * local step, the statistics are accumulated inside the step kernel while z is still in registers
+ * (z is not read back from HBM), for every topology without delay, for the iterations between two
+ * communication rounds of tau-overlap SGP, and for overlap iterations that receive exactly two
+ * messages per node (two out-peers; the very first iteration, which receives nothing, does not
+ * qualify); otherwise the two kernels run one after the other.  The state written is identical to
+ * sgp_step's; the statistics agree with sgp_consensus_stats to rounding (a different reference row
+ * is subtracted before squaring).  The reduction of the fused kernel's partial sums runs on a stream
+ * that the library owns, behind the step kernel.  SYNCHRONISES the stream.
  */
 int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
                    float gamma, float momentum, int64_t k, sgp_stats *host_out,
@@ -325,8 +329,9 @@ const char *sgp_status_string(int status);
 int sgp_last_hip_error(const sgp_handle *h);
 
 /* Measurement utility: static name of the step kernel that the latest successful step on this
- * handle launched ("k_step_one_peer", "k_step_one_peer_stats", "k_step_gather", "k_step_complete",
- * "k_step_delay", "k_step_delay2"; "" before the first step), so that a benchmark can report what
+ * handle launched ("k_step_one_peer", "k_step_gather", "k_step_complete", "k_step_delay",
+ * "k_step_delay2", "k_step_one_peer_h16", and with fused statistics "k_step_one_peer_stats",
+ * "k_step_gather_stats", "k_step_complete_stats", "k_step_delay2_stats"; "" before the first step), so that a benchmark can report what
  * ran instead of re-deriving the library's dispatch. */
 const char *sgp_last_step_kernel(const sgp_handle *h);
 

@@ -234,11 +234,11 @@ int ensure_device(sgp_handle *h)
 
 unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1) / block); }
 
-// Whether a step with statistics can take them inside the step kernel.
-bool fused_stats_applies(const sgp_handle *h, bool gather, bool complete, bool custom, bool adam, bool vec,
-                         long tail)
+// Whether a step with statistics can take them inside the step kernel (conditions common to every
+// kernel family; overlap mode additionally needs exactly two messages per receiver).
+bool fused_stats_applies(const sgp_handle *h, bool adam, bool vec, long tail)
 {
-    return h->delay == 0 && !gather && !complete && !custom && !adam && h->n <= kStatsCache && vec && tail == 0;
+    return !adam && h->n <= kStatsCache && vec && tail == 0;
 }
 
 // Resources of the fused step+statistics path: a stream of its own for the reduction, events, and
@@ -330,8 +330,18 @@ void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 // LDS of the gather kernel: the two weight arrays, then one private column of n values per work-item.
 size_t gather_lds_bytes(int n, int V) { return weight_lds_bytes(n) + (size_t)n * kGatherBlock * V * sizeof(float); }
 
-template <int V, int OPT, bool ZOUT>
-void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S)
+// fin != NULL: the launch carries the statistics (partial table `partial`) and `fin` is attached to
+// the kernel as its completion event.
+template <typename K, typename... Args>
+void launch_step(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t fin, Args... args)
+{
+    if (fin) hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, nullptr, fin, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+}
+
+template <int V, int OPT, bool ZOUT, bool STATS = false>
+void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S,
+                   float *partial = nullptr, hipEvent_t fin = nullptr)
 {
     const size_t lds = gather_lds_bytes(a.n, V);
     dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
@@ -341,21 +351,50 @@ void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, c
         if (lds > 64 * 1024)
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL(kernel, grid, block, lds, a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols,
-                           tab, tabw, S, a.p, a.hp);
+        launch_step(kernel, grid, block, lds, a.stream, fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols,
+                    tab, tabw, S, a.p, a.hp, partial);
     };
-    if (tabw) go(k_step_gather<V, OPT, ZOUT, true>);
-    else go(k_step_gather<V, OPT, ZOUT, false>);
-    *a.name = "k_step_gather";
+    if (tabw) go(k_step_gather<V, OPT, ZOUT, true, STATS>);
+    else go(k_step_gather<V, OPT, ZOUT, false, STATS>);
+    *a.name = STATS ? "k_step_gather_stats" : "k_step_gather";
 }
 
-template <int V, int OPT, bool ZOUT>
-void launch_complete(const StepArgs &a, size_t col0, long ncols)
+template <int V, int OPT, bool ZOUT, bool STATS = false>
+void launch_complete(const StepArgs &a, size_t col0, long ncols, float *partial = nullptr, hipEvent_t fin = nullptr)
 {
-    hipLaunchKernelGGL((k_step_complete<V, OPT, ZOUT>), dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
-                       weight_lds_bytes(a.n), a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols, a.p,
-                       a.hp);
-    *a.name = "k_step_complete";
+    launch_step(k_step_complete<V, OPT, ZOUT, STATS>, dim3(grid_for(ncols, kOpBlock)), dim3(kOpBlock),
+                weight_lds_bytes(a.n), a.stream, fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols, a.p, a.hp,
+                partial);
+    *a.name = STATS ? "k_step_complete_stats" : "k_step_complete";
+}
+
+// The unrolled walk with the statistics taken from registers: one out-peer (or none), or, with
+// msg_prev != NULL, two out-peers under one iteration of delay.
+void launch_walk_stats(const StepArgs &a, int opt, long cols4, int h, int len, float *partial, hipEvent_t fin,
+                       const float *msg_prev = nullptr, float *msg_cur = nullptr, int ha = 0, int hb = 0)
+{
+    static_assert(kStatsStepBlock == kGatherBlock && kStatsStepBlock == kOpBlock,
+                  "every kernel with fused statistics writes one line of partial sums per 64 column groups");
+    auto go = [&](auto kernel) {
+        launch_step(kernel, dim3(grid_for(cols4, kStatsStepBlock)), dim3(kStatsStepBlock), weight_lds_bytes(a.n),
+                    a.stream, fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, cols4, h, len, a.p, a.hp, partial, msg_prev,
+                    msg_cur, ha, hb);
+    };
+    const bool nest = opt == kOptNesterov;
+    if (msg_prev) {
+        if (nest) go(k_step_one_peer_stats<true, false, true>);
+        else go(k_step_one_peer_stats<false, false, true>);
+        *a.name = "k_step_delay2_stats";
+    } else {
+        if (nest) {
+            if (a.cached) go(k_step_one_peer_stats<true, true, false>);
+            else go(k_step_one_peer_stats<true, false, false>);
+        } else {
+            if (a.cached) go(k_step_one_peer_stats<false, true, false>);
+            else go(k_step_one_peer_stats<false, false, false>);
+        }
+        *a.name = "k_step_one_peer_stats";
+    }
 }
 
 template <int V, int OPT, bool ZOUT>
@@ -665,7 +704,11 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     const long cols4 = vec ? (long)(h->d / 4) : 0;             // full 128-bit groups
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
-    const bool use_fused = fused && z_out && sending && fused_stats_applies(h, gather, complete, custom, adam != nullptr, cols4 > 0, tail);
+    // overlap mode: the fused walk exists for exactly two messages per receiver (two out-peers, and
+    // something has been sent already)
+    const bool two_msgs = h->delay != 0 && sending && h->have_msgs && h->L > 0 && S == 3;
+    const bool use_fused = fused && z_out && fused_stats_applies(h, adam != nullptr, cols4 > 0, tail) &&
+                           (h->delay == 0 || !sending || two_msgs);
 
     int rc = ensure_device(h);
     if (rc != SGP_OK) return rc;
@@ -720,11 +763,28 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         SGP_HIP_TRY(h, hipEventRecord(tev[0], st));
     }
 
+    // with fused statistics: the slot's table and weight copy, and the slot's event attached to the
+    // kernel itself as its completion event (no marker of its own on the caller's stream); the
+    // reduction on the library's stream waits for it
+    float *partial = nullptr;
+    hipEvent_t fin = nullptr;
+    if (use_fused) {
+        partial = h->d_partial_f[fused->slot];
+        fin = h->ev_step[fused->slot];
+        a.wop.publish = 1;
+        a.wop.w_snap = h->d_w_snap[fused->slot];
+        fused->G = (int)grid_for(cols4, kStatsStepBlock);
+        fused->hop = 0;                  // slot s holds node s unless a walk says otherwise
+        fused->len = 1;
+    }
+
     if (!sending) {
         // between two communication rounds: a local step, x <- xh, w unchanged (Alg. 2, else branch
         // of the send test), which is the one-peer walk with n cycles of length 1 and weight 1
         a.wop.kind = kWKeep;
         a.p = 1.0f;
+        if (use_fused) launch_walk_stats(a, opt, cols4, 0, 1, partial, fin);
+        else
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
             two_launches([&] { launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, 0, 1); },
                          [&] { launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, 0, 1); });
@@ -733,64 +793,45 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         a.p = 1.0f / (float)n;
         a.wop.kind = kWComplete;
         a.wop.p = a.p;
+        if (use_fused) {
+            if (opt == kOptNesterov) launch_complete<4, kOptNesterov, true, true>(a, 0, cols4, partial, fin);
+            else launch_complete<4, kOptSgd, true, true>(a, 0, cols4, partial, fin);
+        } else
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
             two_launches([&] { launch_complete<4, OPT, ZOUT>(a, 0, cols4); },
                          [&] { launch_complete<1, OPT, ZOUT>(a, tail0, tail); });
         });
-    } else if (custom) {
-        a.wop.kind = kWCustom;
-        a.wop.tab = h->d_cidx;
-        a.wop.tabw = h->d_cw;
-        a.wop.S = h->cS;
+    } else if (custom || gather) {
+        const int *tab = custom ? h->d_cidx : tab_k;
+        const float *tabw = custom ? h->d_cw : nullptr;
+        const int entries = custom ? h->cS : S;
+        a.wop.kind = custom ? kWCustom : kWTable;
+        a.wop.tab = tab;
+        a.wop.tabw = tabw;
+        a.wop.S = entries;
+        if (use_fused) {
+            if (opt == kOptNesterov) launch_gather<4, kOptNesterov, true, true>(a, 0, cols4, tab, tabw, entries, partial, fin);
+            else launch_gather<4, kOptSgd, true, true>(a, 0, cols4, tab, tabw, entries, partial, fin);
+        } else
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, h->d_cidx, h->d_cw, h->cS); },
-                         [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, h->d_cidx, h->d_cw, h->cS); });
+            two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab, tabw, entries); },
+                         [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab, tabw, entries); });
         });
     } else if (h->delay == 0) {
-        if (!gather) {
-            const int hop = s.distinct ? s.uniq[0] % n : 0;
-            const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
-            const int len = n / ncyc;
-            a.wop.kind = kWOnePeer;
-            a.wop.hop = s.distinct ? hop : -1;
-            if (use_fused) {
-                const unsigned Gf = grid_for(cols4, kStatsStepBlock);
-                a.wop.publish = 1;
-                a.wop.w_snap = h->d_w_snap[fused->slot];
-                float *partial = h->d_partial_f[fused->slot];
-                // the slot's event is attached to the kernel itself as its completion event (no marker of
-                // its own on the caller's stream); the reduction on the library's stream waits for it
-                hipEvent_t fin = h->ev_step[fused->slot];
-                auto go = [&](auto kernel) {
-                    hipExtLaunchKernelGGL(kernel, dim3(Gf), dim3(kStatsStepBlock), (uint32_t)weight_lds_bytes(n), st,
-                                          nullptr, fin, 0, x, m, g, z_out, a.wop, n, (size_t)h->ld, cols4, hop, len,
-                                          s.p, hp, partial);
-                };
-                if (opt == kOptNesterov) {
-                    if (cached) go(k_step_one_peer_stats<true, true>);
-                    else go(k_step_one_peer_stats<true, false>);
-                } else {
-                    if (cached) go(k_step_one_peer_stats<false, true>);
-                    else go(k_step_one_peer_stats<false, false>);
-                }
-                kname = "k_step_one_peer_stats";
-                fused->G = (int)Gf;
-                fused->hop = hop;
-                fused->len = len;
-            } else
-            dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-                two_launches([&] { launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, hop, len); },
-                             [&] { launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, hop, len); });
-            });
-        } else {
-            a.wop.kind = kWTable;
-            a.wop.tab = tab_k;
-            a.wop.S = S;
-            dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-                two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab_k, nullptr, S); },
-                             [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab_k, nullptr, S); });
-            });
-        }
+        const int hop = s.distinct ? s.uniq[0] % n : 0;
+        const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
+        const int len = n / ncyc;
+        a.wop.kind = kWOnePeer;
+        a.wop.hop = s.distinct ? hop : -1;
+        if (use_fused) {
+            launch_walk_stats(a, opt, cols4, hop, len, partial, fin);
+            fused->hop = hop;
+            fused->len = len;
+        } else
+        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+            two_launches([&] { launch_one_peer<4, OPT, ZOUT>(a, 0, cols4, hop, len); },
+                         [&] { launch_one_peer<1, OPT, ZOUT>(a, tail0, tail, hop, len); });
+        });
     } else {
         const int *tab_prev = nullptr;
         int ha = 0, hb = 0;          // the previous round's hops, when there are exactly two
@@ -809,6 +850,13 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         a.wop.S = S;
         a.wop.msgw_prev = h->d_msgw[prv];
         a.wop.msgw_cur = h->d_msgw[cur];
+        if (use_fused) {             // two messages per receiver: the stride walk of k_step_delay2
+            const int stride = ((hb - ha) % n + n) % n;
+            const int len = n / gcd_int(n, stride);
+            launch_walk_stats(a, opt, cols4, stride, len, partial, fin, h->d_msg[prv], h->d_msg[cur], ha, hb);
+            fused->hop = stride;
+            fused->len = len;
+        } else
         dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
             two_launches(
                 [&] { launch_delay<4, OPT, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); },

@@ -21,7 +21,7 @@ def host(t):
     return t.detach().cpu().numpy()
 
 
-def run(n, d, ld, peers, delay, iters, mom, seed, spread, w_spread=False, k0=0):
+def run(n, d, ld, peers, delay, iters, mom, seed, spread, w_spread=False, k0=0, complete=False, kernels=None):
     rng = np.random.default_rng(seed)
     base = rng.standard_normal(d).astype(np.float32)
     x = (base[None, :] + spread * rng.standard_normal((n, d))).astype(np.float32)
@@ -36,17 +36,22 @@ def run(n, d, ld, peers, delay, iters, mom, seed, spread, w_spread=False, k0=0):
         out[:, :d] = a
         return dev(out)
     X, U, G, Z, W = pad(x), pad(u), pad(np.zeros_like(x)), pad(np.zeros_like(x)), dev(w)
-    eng = sgp.SGP(n, d, ld, peers=peers, delay=delay)
-    st = O.Delay1State(n, d, np.float32) if delay else None
+    eng = sgp.SGP(n, d, ld, topology=1 if complete else 0, peers=peers, delay=delay)
+    st = O.OsgpState(n, d, np.float32, delay) if delay else None
+    seen = set()
     xo, wo, uo = x.copy(), w.copy(), u.copy()
     for it in range(iters):
         k = k0 + it
         g = (spread * rng.standard_normal((n, d))).astype(np.float32)
         G[:, :d] = dev(g)
         s = eng.step_stats(X, W, U if nest else None, G, Z, 0.1, mom, k, per_node=True)
-        P = O.mixing_matrix(n, peers, k, np.float32)
+        seen.add(eng.last_step_kernel())
+        if complete:
+            P = np.full((n, n), np.float32(1.0) / np.float32(n), dtype=np.float32)
+        else:
+            P = O.mixing_matrix(n, peers, k // max(1, delay), np.float32)
         if delay:
-            zo = O.step_delay1(P, xo, wo, uo if nest else None, g, 0.1, mom, st, nesterov=nest)
+            zo = O.step_osgp(P, xo, wo, uo if nest else None, g, 0.1, mom, st, k, nesterov=nest)
         else:
             zo = O.step(P, xo, wo, uo if nest else None, g, 0.1, mom, nesterov=nest)
         tag = "n=%d d=%d peers=%d delay=%d k=%d" % (n, d, peers, delay, k)
@@ -66,6 +71,8 @@ def run(n, d, ld, peers, delay, iters, mom, seed, spread, w_spread=False, k0=0):
         assert abs(s.zbar_norm - ref["zbar_norm"]) <= 1e-5 * ref["zbar_norm"], tag
     for T in (X, U, G, Z):
         assert (host(T)[:, d:] == 3.5).all()
+    if kernels is not None:
+        assert seen == set(kernels), seen
     eng.close()
 
 
@@ -75,6 +82,67 @@ def test_fused_all_node_counts_and_hops(n):
     run(n, 2052, 2052, 1, 0, L + 1, 0.9, seed=n, spread=1.0, w_spread=True)
 
 
+@pytest.mark.parametrize("n", [3, 4, 5, 8, 13, 16, 32])
+def test_fused_two_peers_blocking(n):
+    L = max(1, (n - 1).bit_length())
+    run(n, 2052, 2052, 2, 0, L + 1, 0.9, seed=n, spread=1.0, w_spread=True, kernels=["k_step_gather_stats"])
+    run(n, 1000, 1024, 3, 0, 3, 0.0, seed=n + 1, spread=1e-3, k0=2, kernels=["k_step_gather_stats"])
+
+
+@pytest.mark.parametrize("n", [3, 4, 5, 8, 13, 16, 32])
+def test_fused_two_peers_one_iteration_of_delay(n):
+    """The first iteration has nothing to receive and takes the table-driven kernel plus a
+    statistics pass; from then on the stride walk carries the statistics."""
+    L = max(1, (n - 1).bit_length())
+    run(n, 2052, 2052, 2, 1, L + 3, 0.9, seed=n, spread=1.0, w_spread=True,
+        kernels=["k_step_delay", "k_step_delay2_stats"])
+    run(n, 1000, 1024, 2, 1, 4, 0.0, seed=n + 1, spread=1e-3, k0=3, kernels=["k_step_delay", "k_step_delay2_stats"])
+
+
+@pytest.mark.parametrize("n", [1, 2, 8, 32])
+def test_fused_complete_graph(n):
+    run(n, 2052, 2052, 1, 0, 3, 0.9, seed=n, spread=1.0, w_spread=True, complete=True,
+        kernels=["k_step_complete_stats"])
+
+
+def test_fused_local_iterations_between_communication_rounds():
+    run(8, 2052, 2052, 2, 2, 7, 0.9, seed=3, spread=0.1, w_spread=True,
+        kernels=["k_step_delay", "k_step_one_peer_stats", "k_step_delay2_stats"])
+    run(16, 1024, 1024, 1, 3, 7, 0.9, seed=4, spread=0.1, kernels=["k_step_delay", "k_step_one_peer_stats"])
+
+
+def test_fused_custom_rows():
+    """Caller-supplied rows (here: a random column-stochastic matrix with three senders per row)."""
+    n, d = 16, 4100
+    rng = np.random.default_rng(8)
+    idx = np.stack([np.sort(rng.choice(n, 3, replace=False)) for _ in range(n)])
+    raw = rng.random((n, 3)).astype(np.float64) + 0.1
+    P = np.zeros((n, n))
+    for i in range(n):
+        P[i, idx[i]] = raw[i]
+    P /= P.sum(0, keepdims=True).clip(1e-30)                     # columns sum to 1 (where a column is used)
+    P32 = P.astype(np.float32)
+    wts = np.stack([P32[i, idx[i]] for i in range(n)])
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    w = (0.5 + rng.random(n)).astype(np.float32)
+    eng = sgp.SGP(n, d, topology=2)
+    eng.set_mixing(idx.tolist(), wts.tolist())
+    X, U, W = dev(x), dev(np.zeros_like(x)), dev(w)
+    Z = torch.empty_like(X)
+    xo, uo, wo = x.copy(), np.zeros_like(x), w.copy()
+    for k in range(3):
+        g = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+        s = eng.step_stats(X, W, U, dev(g), Z, 0.1, 0.9, k, per_node=True)
+        assert eng.last_step_kernel() == "k_step_gather_stats"
+        zo = O.step(P32, xo, wo, uo, g, 0.1, 0.9)
+        assert np.array_equal(host(X), xo) and np.array_equal(host(Z), zo) and np.array_equal(host(W), wo)
+        dist, ref = O.consensus_stats(zo, wo)
+        assert np.abs(np.array(s.per_node) - dist).max() <= 1e-5 * ref["max"]
+        assert abs(s.zbar_norm - ref["zbar_norm"]) <= 1e-5 * ref["zbar_norm"]
+        assert abs(s.w_sum - ref["w_sum"]) <= 1e-6 * ref["w_sum"]
+    eng.close()
+
+
 @pytest.mark.parametrize("spread", [1.0, 1e-3, 1e-6])
 def test_fused_near_consensus_keeps_relative_accuracy(spread):
     run(32, 40000, 40000, 1, 0, 5, 0.9, seed=5, spread=spread)
@@ -82,9 +150,9 @@ def test_fused_near_consensus_keeps_relative_accuracy(spread):
 
 
 @pytest.mark.parametrize("n,d,ld,peers,delay", [(33, 1024, 1024, 1, 0), (8, 1023, 1024, 1, 0),
-                                                 (8, 1026, 1028, 1, 0), (8, 1024, 1024, 2, 0),
-                                                 (8, 1024, 1024, 1, 1), (8, 1024, 1024, 2, 1),
-                                                 (100, 516, 516, 1, 0)])
+                                                 (8, 1026, 1028, 1, 0), (40, 1024, 1024, 2, 0),
+                                                 (8, 1024, 1024, 1, 1), (8, 1022, 1024, 2, 1),
+                                                 (16, 1024, 1024, 3, 1), (100, 516, 516, 1, 0)])
 def test_shapes_outside_the_fused_kernel_fall_back(n, d, ld, peers, delay):
     run(n, d, ld, peers, delay, 4, 0.9, seed=n + d, spread=0.1)
 
