@@ -328,6 +328,12 @@ const char *sgp_status_string(int status);
 /* hipError_t value of the last failed HIP call on this handle (0 if none). */
 int sgp_last_hip_error(const sgp_handle *h);
 
+/* Test hook: the library's next `succeed_first` device allocations (process-wide) succeed, the one
+ * after them fails as if the device were out of memory, later ones succeed again; a negative value
+ * switches the hook off.  Lets a test drive the SGP_ERR_NOMEM paths: a step that fails this way has
+ * launched nothing, and a repeated call picks the set-up up where it stopped. */
+int sgp_debug_fail_alloc(int32_t succeed_first);
+
 /* Measurement utility: static name of the step kernel that the latest successful step on this
  * handle launched ("k_step_one_peer", "k_step_gather", "k_step_complete", "k_step_delay",
  * "k_step_delay2", "k_step_one_peer_h16", and with fused statistics "k_step_one_peer_stats",

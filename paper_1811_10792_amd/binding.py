@@ -36,7 +36,7 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
            "sgp_consensus_stats_noalloc", "sgp_last_step_kernel", "sgp_probe_regions",
-           "sgp_smooth_region_classes", "sgp_step_bf16")
+           "sgp_smooth_region_classes", "sgp_step_bf16", "sgp_debug_fail_alloc")
 
 
 class SgpError(RuntimeError):
@@ -105,6 +105,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_step_kernel_times.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
     lib.sgp_probe_regions.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.POINTER(i32), vp]
     lib.sgp_smooth_region_classes.argtypes = [vp, i32]
+    lib.sgp_debug_fail_alloc.argtypes = [i32]
     lib.sgp_step_bf16.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, i32, vp]
     lib.sgp_last_step_kernel.argtypes = [vp]
     lib.sgp_last_step_kernel.restype = ctypes.c_char_p

@@ -28,6 +28,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -143,6 +144,26 @@ struct sgp_handle {
 
 namespace {
 
+// Device allocation of the library.  Tests can make the next allocations fail (sgp_debug_fail_alloc)
+// to exercise the out-of-memory paths without exhausting the device.
+std::atomic<int> g_allocs_until_failure{-1};   // -1: off; k >= 0: k more allocations succeed, then one fails
+
+template <typename T>
+hipError_t dev_malloc(T **out, size_t bytes)
+{
+    int left = g_allocs_until_failure.load();
+    while (left >= 0) {
+        if (g_allocs_until_failure.compare_exchange_weak(left, left - 1)) {
+            if (left == 0) {
+                *out = nullptr;
+                return hipErrorOutOfMemory;
+            }
+            break;
+        }
+    }
+    return hipMalloc(reinterpret_cast<void **>(out), bytes);
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
@@ -188,7 +209,7 @@ int upload_tables(sgp_handle *h)
     if (!host_tab) return SGP_ERR_NOMEM;
     build_tables(h, host_tab);
     int *fresh = nullptr;
-    hipError_t e = hipMalloc(&fresh, tab_elems * sizeof(int));
+    hipError_t e = dev_malloc(&fresh, tab_elems * sizeof(int));
     if (e == hipSuccess) e = hipMemcpy(fresh, host_tab, tab_elems * sizeof(int), hipMemcpyHostToDevice);
     std::free(host_tab);
     if (e != hipSuccess) {
@@ -213,19 +234,19 @@ int ensure_device(sgp_handle *h)
     h->G = kStatsGridMax;
     const size_t res_bytes = (size_t)kResultSlots * (8 + n) * sizeof(double);
     if (!h->d_done) {
-        SGP_HIP_TRY(h, hipMalloc(&h->d_done, (kStepCounters + kResultSlots) * sizeof(unsigned)));
+        SGP_HIP_TRY(h, dev_malloc(&h->d_done, (kStepCounters + kResultSlots) * sizeof(unsigned)));
         SGP_HIP_TRY(h, hipMemset(h->d_done, 0, (kStepCounters + kResultSlots) * sizeof(unsigned)));
     }
-    if (!h->d_partial) SGP_HIP_TRY(h, hipMalloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float)));
-    if (!h->d_sums) SGP_HIP_TRY(h, hipMalloc(&h->d_sums, (size_t)(n + 1) * sizeof(double)));
-    if (!h->d_result) SGP_HIP_TRY(h, hipMalloc(&h->d_result, res_bytes));
+    if (!h->d_partial) SGP_HIP_TRY(h, dev_malloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float)));
+    if (!h->d_sums) SGP_HIP_TRY(h, dev_malloc(&h->d_sums, (size_t)(n + 1) * sizeof(double)));
+    if (!h->d_result) SGP_HIP_TRY(h, dev_malloc(&h->d_result, res_bytes));
     if (!h->h_result)
         SGP_HIP_TRY(h, hipHostMalloc(reinterpret_cast<void **>(&h->h_result), res_bytes, hipHostMallocDefault));
     if (h->delay) {
         size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
         for (int b = 0; b < 2; ++b) {
-            if (!h->msg_external && !h->d_msg[b]) SGP_HIP_TRY(h, hipMalloc(&h->d_msg[b], bytes));
-            if (!h->d_msgw[b]) SGP_HIP_TRY(h, hipMalloc(&h->d_msgw[b], (size_t)n * sizeof(float)));
+            if (!h->msg_external && !h->d_msg[b]) SGP_HIP_TRY(h, dev_malloc(&h->d_msg[b], bytes));
+            if (!h->d_msgw[b]) SGP_HIP_TRY(h, dev_malloc(&h->d_msgw[b], (size_t)n * sizeof(float)));
         }
     }
     h->dev_ready = true;
@@ -251,10 +272,10 @@ int ensure_fused(sgp_handle *h)
     if (!h->side) SGP_HIP_TRY(h, hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking));
     for (int s = 0; s < kResultSlots; ++s) {
         if (!h->d_partial_f[s])
-            SGP_HIP_TRY(h, hipMalloc(&h->d_partial_f[s], (size_t)(kStatsCache + 1) * Gf * sizeof(float)));
+            SGP_HIP_TRY(h, dev_malloc(&h->d_partial_f[s], (size_t)(kStatsCache + 1) * Gf * sizeof(float)));
         if (!h->d_sums_f[s])
-            SGP_HIP_TRY(h, hipMalloc(&h->d_sums_f[s], (size_t)kSlotSumBlocks * (kStatsCache + 1) * sizeof(double)));
-        if (!h->d_w_snap[s]) SGP_HIP_TRY(h, hipMalloc(&h->d_w_snap[s], (size_t)h->n * sizeof(float)));
+            SGP_HIP_TRY(h, dev_malloc(&h->d_sums_f[s], (size_t)kSlotSumBlocks * (kStatsCache + 1) * sizeof(double)));
+        if (!h->d_w_snap[s]) SGP_HIP_TRY(h, dev_malloc(&h->d_w_snap[s], (size_t)h->n * sizeof(float)));
     }
     h->fused_ready = true;
     return SGP_OK;
@@ -561,8 +582,8 @@ int sgp_set_mixing(sgp_handle *h, const int32_t *in_idx, const float *in_weight,
     // the new rows are complete before the old ones are released
     int *idx = nullptr;
     float *wts = nullptr;
-    hipError_t e = hipMalloc(&idx, cnt * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc(&wts, cnt * sizeof(float));
+    hipError_t e = dev_malloc(&idx, cnt * sizeof(int));
+    if (e == hipSuccess) e = dev_malloc(&wts, cnt * sizeof(float));
     if (e == hipSuccess) e = hipMemcpy(idx, in_idx, cnt * sizeof(int), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(wts, in_weight, cnt * sizeof(float), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
@@ -607,6 +628,12 @@ int sgp_set_message_buffers(sgp_handle *h, float *buf0, float *buf1)
 }
 
 int sgp_last_hip_error(const sgp_handle *h) { return h ? h->last_hip : 0; }
+
+int sgp_debug_fail_alloc(int32_t succeed_first)
+{
+    g_allocs_until_failure.store(succeed_first < 0 ? -1 : succeed_first);
+    return SGP_OK;
+}
 
 const char *sgp_last_step_kernel(const sgp_handle *h) { return h ? h->last_kernel : ""; }
 
@@ -1343,7 +1370,7 @@ int sgp_probe_regions(void *arena, int64_t arena_bytes, int64_t granule_bytes, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char *base = static_cast<unsigned char *>(arena);
     rc = sgp_set_kernel_timing(h, 1);
-    if (rc == SGP_OK && hipMalloc(&w_dev, kProbeNodes * sizeof(float)) != hipSuccess) rc = SGP_ERR_NOMEM;
+    if (rc == SGP_OK && dev_malloc(&w_dev, kProbeNodes * sizeof(float)) != hipSuccess) rc = SGP_ERR_NOMEM;
     for (int c = 0; c < max_classes && rc == SGP_OK; ++c) {
         int ref = -1;
         for (int i = 0; i < count && ref < 0; ++i)
