@@ -10,9 +10,12 @@ sgp_step_stats; --separate-stats: one sgp_step call plus one sgp_consensus_stats
 small rotating pool of pre-drawn gradient buffers are resident in HBM before the timed region;
 drawing gradients is not part of the step (g is an input of the method).
 
-Prints ONE JSON line: node-parameter updates per second (n*d*K / wall time of the K steps),
-the roofline of the dominant kernel (the step kernel, timed with HIP events on the stream it
-runs on), and the CPU oracle timed on a bounded slice of the same workload.
+Prints ONE JSON line: node-parameter updates per second (n*d*K / wall time of the K steps, a timed
+region that holds the steps and nothing else), the roofline of the dominant kernel (the step
+kernel, timed in a second pass of the same steps with HIP events on the stream it runs on) with the
+whole-step fraction beside it, the same steps with ordinary allocations instead of the region-aware
+placement, and the CPU oracle timed at the workload's full size where the host can hold it (with
+all cores) and on a slice (with one core).
 """
 import argparse
 import json
@@ -366,7 +369,7 @@ def main():
                                      "1-peer SGP 16 / 32 nodes 75.9 % in 3.2 h / 75.0 % in 1.7 h; AllReduce SGD "
                                      "76.3 % in 8.5 h / 76.2 % in 5.1 h; no per-iteration update throughput is published"}
     eng.close()
-    del X, U, Z, V2, pool, alloc
+    del X, U, Z, V2, pool, alloc, G      # every view into the arena, so that it is really released
     torch.cuda.empty_cache()
     if args.placement == "regions" and not args.no_default_placement and not h16:
         out["default_placement"] = default_placement_leg(wl, ld, args, bpu)

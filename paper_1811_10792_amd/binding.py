@@ -200,6 +200,7 @@ class SGP:
         if getattr(self, "_h", None) is not None and self._h.value:
             self._lib.sgp_destroy(self._h)
             self._h = ctypes.c_void_p()
+        self._msg_keepalive = None
 
     def __del__(self):
         try:
