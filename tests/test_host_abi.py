@@ -121,3 +121,30 @@ def test_schedule_of_tau_overlap_advances_once_per_round(lib):
             assert wt.value == ref_w
     assert lib.sgp_set_biased(h, 1) == 0 and lib.sgp_set_biased(None, 1) == binding.SGP_ERR_INVALID_ARG
     assert lib.sgp_destroy(h) == 0
+
+
+def test_region_probe_host_paths(lib):
+    """Argument checks of sgp_probe_regions and the cases it answers without touching the device:
+    fewer than two granules, or granules too small for the probe problem, are one class."""
+    import ctypes
+    cls = (ctypes.c_int32 * 8)(*([7] * 8))
+    ms = (ctypes.c_float * 8)(*([1.0] * 8))
+    st = ctypes.c_int32(5)
+    fake = 1 << 20                                   # never dereferenced on these paths
+    G = 1 << 30
+    f = lib.sgp_probe_regions
+    assert f(None, 8 * G, G, 4, cls, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    assert f(fake, 8 * G, G, 4, None, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    assert f(fake, 8 * G, G + 1, 4, cls, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    assert f(fake, G // 2, G, 4, cls, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    assert f(fake, 8 * G, G, 0, cls, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    assert f(fake + 4, 8 * G, G, 4, cls, ms, ctypes.byref(st), None) == binding.SGP_ERR_INVALID_ARG
+    # eight granules of 1 GiB: the probe problem (four arrays of 512 MiB) does not fit one granule
+    assert f(fake, 8 * G, G, 4, cls, ms, ctypes.byref(st), None) == binding.SGP_OK
+    assert list(cls) == [0] * 8 and list(ms) == [0.0] * 8 and st.value == 0
+    # a single granule
+    cls[0] = 7
+    assert f(fake, 8 * G, 8 * G, 4, cls, None, ctypes.byref(st), None) == binding.SGP_OK
+    assert cls[0] == 0 and st.value == 0
+    assert lib.sgp_smooth_region_classes(None, 0) == binding.SGP_OK
+    assert lib.sgp_smooth_region_classes(None, 3) == binding.SGP_ERR_INVALID_ARG

@@ -59,3 +59,65 @@ def test_two_handles_on_two_streams():
             assert np.array_equal(host(s["W"]), s["w"]) and np.array_equal(host(s["U"]), s["u"])
     for s in state:
         s["eng"].close()
+
+
+def test_two_handles_pipelined_statistics_on_two_streams():
+    """Each handle reduces its fused statistics on a stream of its own behind its step kernels;
+    two handles run their begin / end pipelines interleaved on two caller streams."""
+    rng = np.random.default_rng(13)
+    cfg = [dict(n=32, d=200_000, peers=1, delay=0), dict(n=16, d=100_000, peers=2, delay=1)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    state = []
+    for c in cfg:
+        n, d = c["n"], c["d"]
+        x = rng.standard_normal((n, d)).astype(np.float32)
+        gs = [(0.2 * rng.standard_normal((n, d))).astype(np.float32) for _ in range(2)]
+        state.append(dict(x=x, u=np.zeros_like(x), w=np.ones(n, np.float32), gs=gs,
+                          X=dev(x), U=dev(np.zeros_like(x)), W=dev(np.ones(n, np.float32)),
+                          Z=dev(np.zeros_like(x)), G=[dev(g) for g in gs],
+                          eng=sgp.SGP(n, d, peers=c["peers"], delay=c["delay"]),
+                          st=O.OsgpState(n, d, np.float32, 1) if c["delay"] else None, got=[]))
+    torch.cuda.synchronize()
+    iters = 7
+    for k in range(iters):
+        for s, stream in zip(state, streams):
+            s["eng"].step_stats_begin(s["X"], s["W"], s["U"], s["G"][k % 2], s["Z"], 0.05, 0.9, k, stream=stream)
+            if k > 0:
+                s["got"].append(s["eng"].step_stats_end(per_node=True))
+    for s in state:
+        s["got"].append(s["eng"].step_stats_end(per_node=True))
+    torch.cuda.synchronize()
+    for c, s in zip(cfg, state):
+        for k in range(iters):
+            P = O.mixing_matrix(c["n"], c["peers"], k, np.float32)
+            if c["delay"]:
+                zo = O.step_osgp(P, s["x"], s["w"], s["u"], s["gs"][k % 2], 0.05, 0.9, s["st"], k)
+            else:
+                zo = O.step(P, s["x"], s["w"], s["u"], s["gs"][k % 2], 0.05, 0.9)
+            dist, ref = O.consensus_stats(zo, s["w"])
+            got = s["got"][k]
+            assert np.abs(np.array(got.per_node) - dist).max() <= 1e-5 * ref["max"], (c, k)
+            assert abs(got.w_sum - ref["w_sum"]) <= 1e-6 * ref["w_sum"], (c, k)     # the weights of ITS step
+        assert np.array_equal(host(s["X"]), s["x"]) and np.array_equal(host(s["W"]), s["w"])
+        s["eng"].close()
+
+
+def test_weights_changed_by_the_caller_between_steps_are_honoured():
+    """The step kernels read the push-sum weights from the caller's array at every call (and write
+    the new ones back at the end of the launch): a caller may overwrite w between steps."""
+    n, d = 16, 50_000
+    rng = np.random.default_rng(14)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    u, w = np.zeros_like(x), np.ones(n, np.float32)
+    X, U, W, Z = dev(x), dev(u), dev(w), dev(np.zeros_like(x))
+    eng = sgp.SGP(n, d, peers=2, delay=1)
+    st = O.OsgpState(n, d, np.float32, 1)
+    for k in range(6):
+        g = (0.1 * rng.standard_normal((n, d))).astype(np.float32)
+        if k == 3:                                   # the caller rescales every node's weight
+            w = (w * np.float32(1.5)).astype(np.float32)
+            W.copy_(dev(w))
+        eng.step(X, W, U, dev(g), Z, 0.05, 0.9, k)
+        zo = O.step_osgp(O.mixing_matrix(n, 2, k, np.float32), x, w, u, g, 0.05, 0.9, st, k)
+        assert np.array_equal(host(W), w) and np.array_equal(host(Z), zo) and np.array_equal(host(X), x)
+    eng.close()
