@@ -21,7 +21,7 @@
 //   step_gather.inc         several out-peers / caller-supplied rows: private LDS columns
 //   step_complete.inc       complete graph
 //   step_overlap.inc        tau-overlap SGP: own share now, messages of the previous round
-//   weights.inc             stand-alone de-bias, reference copy
+//   debias_copy.inc         stand-alone de-bias, reference copy
 //   stats.inc               stand-alone consensus statistics and the final reductions
 //   sgp.hip                 handle, launchers, C ABI
 #include <hip/hip_runtime.h>
@@ -78,7 +78,7 @@ constexpr int kStatsCache = 32;   // nodes whose z the small-n statistics kernel
 #include "step_gather.inc"
 #include "step_complete.inc"
 #include "step_overlap.inc"
-#include "weights.inc"
+#include "debias_copy.inc"
 #include "stats.inc"
 
 }  // namespace
