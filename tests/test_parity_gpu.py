@@ -182,6 +182,12 @@ def test_multi_peer_gather(n, peers):
     run_both(n, 520, 520, peers, 0, min(L + 1, 5), 0.1, 0.9, seed=n + peers, w_spread=True)
 
 
+@pytest.mark.parametrize("peers,delay", [(1, 0), (1, 1), (2, 1)])
+def test_largest_node_count(peers, delay):
+    """n = SGP_MAX_NODES: every block forms 1024 weights (16 per work-item of a single-wave block)."""
+    run_both(1024, 24, 24, peers, delay, 3, 0.1, 0.9, seed=peers + delay, w_spread=True, k0=9)
+
+
 @pytest.mark.parametrize("n,d", [(150, 132), (151, 132), (600, 36)])
 def test_multi_peer_gather_at_the_node_limits(n, d):
     """The private LDS columns of the gather kernel: 128-bit accesses up to n = 150, scalar ones up
@@ -325,7 +331,7 @@ def test_placement_probe_finds_regions_and_separates_the_written_streams():
     alloc.reset()
 
 
-def _full_size_spot_check(wl, steps, count=3000):
+def _full_size_spot_check(wl, steps, count=3000, force_stats=False):
     """Model-sized state generated on the device, the launch configuration the benchmark times;
     the oracle recomputes a sample of coordinates (coordinates are independent, so a column
     slice of the oracle is exact), including the first tile and the ragged tail."""
@@ -361,7 +367,7 @@ def _full_size_spot_check(wl, steps, count=3000):
         g = host(G[:, cidx])
         if adam:
             eng.step_adam(X, W, U, V2, G, Z, wl.gamma, 0.9, 0.98, 1e-8, k + 1, k)
-        elif wl.stats_each_step:                               # what the benchmark calls
+        elif wl.stats_each_step or force_stats:                # what the benchmark calls
             s_fused = eng.step_stats(X, W, U, G, Z, wl.gamma, wl.momentum, k, per_node=True)
         else:
             eng.step(X, W, U, G, Z, wl.gamma, wl.momentum, k)
@@ -380,6 +386,21 @@ def _full_size_spot_check(wl, steps, count=3000):
         same(host(Z[:, cidx]), zo, "%s z k=%d" % (wl.name, k))
         same(host(U[:, cidx]), uo, "%s u k=%d" % (wl.name, k))
         same(host(W), wo, "%s w k=%d" % (wl.name, k))
+    if force_stats and not wl.stats_each_step:
+        # too large for the host oracle in reasonable time: the fused kernel's statistics against
+        # the stand-alone pass over the z it wrote (itself checked against the oracle at the sizes
+        # the host can handle), and against the oracle on the first 2^20 coordinates
+        assert eng.last_step_kernel().endswith("_stats")
+        s_full = eng.consensus_stats(Z, W, per_node=True)
+        assert np.abs(np.array(s_fused.per_node) - np.array(s_full.per_node)).max() <= 1e-5 * s_full.dist_max
+        assert abs(s_fused.zbar_norm - s_full.zbar_norm) <= 1e-5 * s_full.zbar_norm
+        assert s_fused.w_sum == s_full.w_sum and s_fused.argmax == s_full.argmax
+        dsl = 1 << 20
+        sl = sgp.SGP(n, dsl, ld)
+        s = sl.consensus_stats(Z, W, per_node=True)
+        dist, ref = O.consensus_stats(host(Z[:, :dsl]), wo)
+        assert np.abs(np.array(s.per_node) - dist).max() <= 1e-5 * dist.max()
+        sl.close()
     if wl.stats_each_step:
         # the statistics the fused kernel returned with the last step, against the oracle on the
         # whole z it wrote (a few seconds of host time), and the stand-alone pass on the same z
@@ -479,6 +500,14 @@ def test_full_size_config4_whole_run_of_50_iterations():
 
 def test_full_size_config5_n16_transformer_two_peer_overlap():
     _full_size_spot_check(syn.WORKLOADS["c5_n16_transformer_2peer_overlap"], steps=3)
+
+
+def test_full_size_config5_with_fused_statistics():
+    _full_size_spot_check(syn.WORKLOADS["c5_n16_transformer_2peer_overlap"], steps=3, force_stats=True)
+
+
+def test_full_size_two_peer_blocking_with_fused_statistics():
+    _full_size_spot_check(syn.WORKLOADS["x4_n32_resnet50_2peer"], steps=2, force_stats=True)
 
 
 def test_full_size_transformer_two_peer_tau2():
