@@ -26,6 +26,9 @@
  * 80 % of the HBM peak, with back-to-back allocations 64 %.  The library takes the pointers as they
  * come; sgp_probe_regions (below) finds the regions of a caller's arena by timing, so that the caller
  * can carve x, m and z out of three different ones (the Python package's placement module does that).
+ * State arrays are streamed past the caches (non-temporal accesses), except for problems whose four
+ * arrays together stay below 160 MiB and can live in the last-level cache from one iteration to the
+ * next: those are accessed with ordinary loads and stores (chosen at launch time).
  * Arithmetic is IEEE binary32, round to nearest even, every
  * operation rounded separately (no fused multiply-add), correctly rounded division, subnormals
  * kept.  Sums over senders are taken in ascending sender index.
