@@ -394,6 +394,37 @@ int sgp_probe_regions(void *arena, int64_t arena_bytes, int64_t granule_bytes, i
  * from 0 in order of first appearance.  Errors: SGP_ERR_INVALID_ARG (null with count > 0, count < 0). */
 int sgp_smooth_region_classes(int32_t *class_of_granule, int32_t count);
 
+/*
+ * Host-only: carves arrays out of an arena whose granules sgp_probe_regions has classified, so that
+ * arrays which are written at the same time land in different regions.  No device call is made; the
+ * offsets are relative to the arena's start and multiples of 4096.
+ *   sgp_placer_create : class_of_granule [count] as sgp_probe_regions wrote it, granule_bytes as given there
+ *   sgp_placer_take   : a fresh range of nbytes for an array in the given role.  Roles: x, u (the
+ *                       array `m` of sgp_step) and z are the three written streams and go to three
+ *                       different regions, the largest regions first; g is read-only and shares the
+ *                       region of x; the two message buffers of overlap mode go with u and with x;
+ *                       Adam's second moment with z.  Inside a region the interiors of long runs of
+ *                       granules are used before their edge granules (which may straddle a region
+ *                       boundary) and before short runs.  When the preferred region is full, any
+ *                       other with room is taken; *class_out (nullable) tells which region it was.
+ *                       SGP_ERR_NOMEM when nothing fits.
+ *   sgp_placer_reset  : forgets every range handed out.
+ * Errors: SGP_ERR_INVALID_ARG, SGP_ERR_NOMEM.
+ */
+typedef struct sgp_placer sgp_placer;
+#define SGP_ROLE_X 0
+#define SGP_ROLE_G 1
+#define SGP_ROLE_U 2
+#define SGP_ROLE_Z 3
+#define SGP_ROLE_MSG0 4
+#define SGP_ROLE_MSG1 5
+#define SGP_ROLE_V 6
+#define SGP_ROLE_COUNT 7
+int sgp_placer_create(sgp_placer **out, const int32_t *class_of_granule, int32_t count, int64_t granule_bytes);
+int sgp_placer_destroy(sgp_placer *p);
+int sgp_placer_reset(sgp_placer *p);
+int sgp_placer_take(sgp_placer *p, int32_t role, int64_t nbytes, int64_t *offset_out, int32_t *class_out);
+
 /* Measurement utility: plain 128-bit streaming copy of nbytes (multiple of 16, both pointers
  * 16-byte aligned, device memory) on `stream`.  Serves as the known-size reference when
  * hardware traffic counters are scaled, and as the practical bandwidth ceiling of the part. */

@@ -36,7 +36,8 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_set_mixing", "sgp_set_weight_decay", "sgp_step_adam",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
            "sgp_consensus_stats_noalloc", "sgp_last_step_kernel", "sgp_probe_regions",
-           "sgp_smooth_region_classes", "sgp_step_bf16", "sgp_debug_fail_alloc")
+           "sgp_smooth_region_classes", "sgp_step_bf16", "sgp_debug_fail_alloc",
+           "sgp_placer_create", "sgp_placer_destroy", "sgp_placer_reset", "sgp_placer_take")
 
 
 class SgpError(RuntimeError):
@@ -106,6 +107,10 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_probe_regions.argtypes = [vp, i64, i64, i32, vp, vp, ctypes.POINTER(i32), vp]
     lib.sgp_smooth_region_classes.argtypes = [vp, i32]
     lib.sgp_debug_fail_alloc.argtypes = [i32]
+    lib.sgp_placer_create.argtypes = [ctypes.POINTER(vp), vp, i32, i64]
+    lib.sgp_placer_destroy.argtypes = [vp]
+    lib.sgp_placer_reset.argtypes = [vp]
+    lib.sgp_placer_take.argtypes = [vp, i32, i64, ctypes.POINTER(i64), ctypes.POINTER(i32)]
     lib.sgp_step_bf16.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, i32, vp]
     lib.sgp_last_step_kernel.argtypes = [vp]
     lib.sgp_last_step_kernel.restype = ctypes.c_char_p
@@ -182,6 +187,44 @@ def sgp_smooth_region_classes(classes):
     _check(load_library().sgp_smooth_region_classes(ctypes.addressof(buf), len(classes)),
            "sgp_smooth_region_classes")
     return list(buf[:len(classes)])
+
+
+ROLES = {"x": 0, "g": 1, "u": 2, "z": 3, "msg0": 4, "msg1": 5, "v": 6}
+
+
+class RegionPlacer:
+    """Owner of one sgp_placer: hands out byte offsets into a probed arena (host-only)."""
+
+    def __init__(self, classes, granule_bytes: int):
+        self._lib = load_library()
+        self._p = ctypes.c_void_p()
+        buf = (ctypes.c_int32 * max(1, len(classes)))(*[int(c) for c in classes])
+        _check(self._lib.sgp_placer_create(ctypes.byref(self._p), ctypes.addressof(buf), len(classes),
+                                           granule_bytes), "sgp_placer_create")
+
+    def take(self, role: str, nbytes: int):
+        """(offset, region class) of a fresh range for an array in the given role; MemoryError when
+        nothing fits."""
+        off, cls = ctypes.c_int64(), ctypes.c_int32()
+        rc = self._lib.sgp_placer_take(self._p, ROLES[role], nbytes, ctypes.byref(off), ctypes.byref(cls))
+        if rc == SGP_ERR_NOMEM:
+            raise MemoryError("arena exhausted")
+        _check(rc, "sgp_placer_take")
+        return off.value, cls.value
+
+    def reset(self) -> None:
+        _check(self._lib.sgp_placer_reset(self._p), "sgp_placer_reset")
+
+    def close(self) -> None:
+        if getattr(self, "_p", None) is not None and self._p.value:
+            self._lib.sgp_placer_destroy(self._p)
+            self._p = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class SGP:

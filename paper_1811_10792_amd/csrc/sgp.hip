@@ -35,6 +35,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "sgp.h"
@@ -1311,6 +1312,122 @@ int sgp_smooth_region_classes(int32_t *class_of_granule, int32_t count)
         cls[i] = pos;
     }
     return SGP_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// Carving arrays out of a probed arena (host-only integer logic).
+// ------------------------------------------------------------------------------------------
+struct sgp_placer {
+    int64_t granule;
+    std::vector<int32_t> classes;
+    // free byte ranges [start, end) per class, in the order they are tried
+    std::vector<std::vector<std::pair<int64_t, int64_t>>> free_ranges;
+    std::vector<int32_t> order;   // classes by capacity, largest first
+};
+
+namespace {
+
+void placer_fill(sgp_placer *p)
+{
+    const int count = (int)p->classes.size();
+    int ncls = 0;
+    for (int32_t c : p->classes) ncls = std::max(ncls, c + 1);
+    const int64_t g = p->granule;
+    p->free_ranges.assign((size_t)ncls, {});
+    std::vector<int64_t> capacity((size_t)ncls, 0);
+    for (int c = 0; c < ncls; ++c) {
+        std::vector<std::pair<int, int>> runs;   // (first granule, length) of the maximal runs of class c
+        for (int i = 0; i < count;) {
+            if (p->classes[i] != c) { ++i; continue; }
+            int j = i;
+            while (j < count && p->classes[j] == c) ++j;
+            runs.push_back({i, j - i});
+            capacity[c] += (int64_t)(j - i) * g;
+            i = j;
+        }
+        std::stable_sort(runs.begin(), runs.end(),
+                         [](const std::pair<int, int> &a, const std::pair<int, int> &b) { return a.second > b.second; });
+        // the interiors of the long runs first, longest first (a granule at the edge of a run may
+        // straddle a region boundary, and a short run may be a timing outlier), then what was
+        // trimmed off, then the short runs
+        std::vector<std::pair<int64_t, int64_t>> inner, edges, shorts;
+        for (const auto &r : runs) {
+            const int64_t s0 = r.first, k = r.second;
+            if (k >= 4) {
+                inner.push_back({(s0 + 1) * g, (s0 + k - 1) * g});
+                edges.push_back({s0 * g, (s0 + 1) * g});
+                edges.push_back({(s0 + k - 1) * g, (s0 + k) * g});
+            } else {
+                shorts.push_back({s0 * g, (s0 + k) * g});
+            }
+        }
+        auto &dst = p->free_ranges[c];
+        dst.insert(dst.end(), inner.begin(), inner.end());
+        dst.insert(dst.end(), edges.begin(), edges.end());
+        dst.insert(dst.end(), shorts.begin(), shorts.end());
+    }
+    p->order.resize((size_t)ncls);
+    for (int c = 0; c < ncls; ++c) p->order[c] = c;
+    std::stable_sort(p->order.begin(), p->order.end(),
+                     [&](int32_t a, int32_t b) { return capacity[a] > capacity[b]; });
+}
+
+}  // namespace
+
+extern "C" {
+
+int sgp_placer_create(sgp_placer **out, const int32_t *class_of_granule, int32_t count, int64_t granule_bytes)
+{
+    if (!out) return SGP_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!class_of_granule || count < 1 || granule_bytes < 4096 || (granule_bytes & 4095)) return SGP_ERR_INVALID_ARG;
+    for (int i = 0; i < count; ++i)
+        if (class_of_granule[i] < 0 || class_of_granule[i] > 1024) return SGP_ERR_INVALID_ARG;
+    sgp_placer *p = new (std::nothrow) sgp_placer();
+    if (!p) return SGP_ERR_NOMEM;
+    p->granule = granule_bytes;
+    p->classes.assign(class_of_granule, class_of_granule + count);
+    placer_fill(p);
+    *out = p;
+    return SGP_OK;
+}
+
+int sgp_placer_destroy(sgp_placer *p)
+{
+    delete p;
+    return SGP_OK;
+}
+
+int sgp_placer_reset(sgp_placer *p)
+{
+    if (!p) return SGP_ERR_INVALID_ARG;
+    placer_fill(p);
+    return SGP_OK;
+}
+
+int sgp_placer_take(sgp_placer *p, int32_t role, int64_t nbytes, int64_t *offset_out, int32_t *class_out)
+{
+    // which of the regions (ranked by capacity) a role prefers: the written streams x, u, z go to
+    // three different ones; g is read-only and shares the region of x; the message buffers of overlap
+    // mode go with u and with x (one written into the region of z measured 2.5 % slower); Adam's
+    // second moment goes with z
+    static const int kWant[SGP_ROLE_COUNT] = {0, 0, 1, 2, 1, 0, 2};
+    if (!p || !offset_out || role < 0 || role >= SGP_ROLE_COUNT || nbytes < 1) return SGP_ERR_INVALID_ARG;
+    const int64_t need = (nbytes + 4095) / 4096 * 4096;
+    const int ncls = (int)p->order.size();
+    for (int j = 0; j < ncls; ++j) {          // the preferred region, then any other with room
+        const int32_t cls = p->order[(size_t)((kWant[role] + j) % ncls)];
+        for (auto &run : p->free_ranges[(size_t)cls])
+            if (run.second - run.first >= need) {
+                *offset_out = run.first;
+                run.first += need;
+                if (class_out) *class_out = cls;
+                return SGP_OK;
+            }
+    }
+    return SGP_ERR_NOMEM;
 }
 
 // Times the probe problem with its state arrays in granule `ref` and z in granule `cand`: median

@@ -8,13 +8,14 @@ runs at 6.45 TB/s, with everything in one region at 5.2 TB/s.  A plain 1R+1W cop
 affected (6.56 vs 6.68 TB/s).
 
 User space cannot see physical addresses, so nothing is assumed about the map: one arena covering
-most of the device memory is allocated, the regions are found by timing (`probe_regions`), and the
-arrays are carved out of the arena so that the write streams land in different regions.
+most of the device memory is allocated here (a torch tensor), the library finds its regions by timing
+(sgp_probe_regions) and carves the arrays out of it so that the write streams land in different
+regions (sgp_placer_*); this module only owns the memory and turns offsets into tensors.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import Dict, List, Optional, Sequence, Tuple
+from typing import Dict, List, Optional, Tuple
 
 GIB = 1 << 30
 
@@ -69,47 +70,23 @@ def probe_regions(arena: Arena, granule: int = 8 * GIB, max_classes: int = 4) ->
 
 
 class Placer:
-    """Hands out contiguous arena ranges inside a requested region class."""
+    """Hands out arrays carved from the arena by role; the carving itself (which region a role
+    prefers, interiors of long runs first, fall-back to any region with room) is the library's
+    sgp_placer_* (host-only C ABI), this class turns its byte offsets into tensors."""
 
     def __init__(self, arena: Arena, regions: RegionMap):
+        from .binding import RegionPlacer
         self.arena, self.regions = arena, regions
-        ncls = max(regions.classes) + 1
-        # free ranges per class as [start_byte, end_byte), in the order they are tried: the interiors
-        # of the long runs first, longest first (a granule at the edge of a run may straddle a region
-        # boundary, and a short run may be a timing outlier), then what was trimmed off, then short runs
-        g = regions.granule
-        self.free: Dict[int, List[List[int]]] = {}
-        for c in range(ncls):
-            inner, edges, short = [], [], []
-            for s0, k in sorted(regions.runs(c), key=lambda r: -r[1]):
-                if k >= 4:
-                    inner.append([(s0 + 1) * g, (s0 + k - 1) * g])
-                    edges += [[s0 * g, (s0 + 1) * g], [(s0 + k - 1) * g, (s0 + k) * g]]
-                else:
-                    short.append([s0 * g, (s0 + k) * g])
-            self.free[c] = inner + edges + short
-        # classes ordered by capacity, largest first
-        self.order = sorted(range(ncls), key=lambda c: -regions.capacity(c))
+        self._c = RegionPlacer(regions.classes, regions.granule)
 
-    def take(self, nbytes: int, cls: int) -> Optional[int]:
-        """Byte offset of a fresh 4 KiB-aligned range of `nbytes` in class `cls`, or None."""
-        need = (nbytes + 4095) // 4096 * 4096
-        for run in self.free.get(cls, []):
-            if run[1] - run[0] >= need:
-                off = run[0]
-                run[0] += need
-                return off
-        return None
+    def floats(self, n: int, ld: int, role: str):
+        """[n, ld] float32 tensor for the array `role` ("x", "g", "u", "z", "msg0", "msg1", "v") and
+        the region class it landed in; MemoryError when the arena is exhausted."""
+        off, cls = self._c.take(role, n * ld * 4)
+        return self.arena.floats(off, n, ld), cls
 
-    def floats(self, n: int, ld: int, want: int):
-        """[n, ld] float32 tensor in the `want`-th largest region class (wrapping), falling back to
-        any class with room."""
-        tries = [self.order[(want + j) % len(self.order)] for j in range(len(self.order))]
-        for cls in tries:
-            off = self.take(n * ld * 4, cls)
-            if off is not None:
-                return self.arena.floats(off, n, ld), cls
-        raise MemoryError("arena exhausted")
+    def reset(self) -> None:
+        self._c.reset()
 
 
 def make_placer(reserve_bytes: int = 6 * GIB, device="cuda", min_bytes: int = 0):
@@ -136,8 +113,6 @@ class StateAllocator:
     message buffers of overlap mode go with u ("msg0") and with x ("msg1"): a message buffer written
     into the region of z measured 2.5 % slower (17.5 against 17.1 ms at n = 16, d = 213 M)."""
 
-    ROLE_CLASS = {"x": 0, "g": 0, "u": 1, "msg0": 1, "z": 2, "msg1": 0, "v": 2}
-
     def __init__(self, mode: str = "regions", device="cuda"):
         self.device = device
         self.placer, self.regions = (make_placer(device=device) if mode == "regions" else (None, None))
@@ -150,14 +125,14 @@ class StateAllocator:
         import torch
         if self.placer is None:
             return torch.empty((n, ld), dtype=torch.float32, device=self.device)
-        t, cls = self.placer.floats(n, ld, self.ROLE_CLASS[role])
+        t, cls = self.placer.floats(n, ld, role)
         self.placed[name or role] = cls
         return t
 
     def reset(self) -> None:
         """Forgets every array handed out so far (their memory will be handed out again)."""
         if self.placer is not None:
-            self.placer = Placer(self.placer.arena, self.regions)
+            self.placer.reset()
         self.placed = {}
 
     def describe(self) -> dict:
