@@ -42,7 +42,7 @@ def draw(seed):
     return c, r
 
 
-@pytest.mark.parametrize("seed", range(80))
+@pytest.mark.parametrize("seed", range(240))
 def test_random_configuration(seed):
     c, rng = draw(seed)
     n, d, ld, tau = c["n"], c["d"], c["ld"], c["tau"]
