@@ -191,7 +191,7 @@ int sgp_reset(sgp_handle *h);
  * allocates nothing, records no memset and only launches kernels on `stream`, so a run of iterations
  * can be captured into a graph and replayed.  Measured on MI355X this no longer pays: since a step
  * became one launch, replaying a captured cycle of the schedule was no faster than eager calls
- * (35.0 against 33.6 us per iteration at n = 8, d = 2^20; 10.5 against 9.2 us at n = 4, d = 1024).
+ * (31.8 against 30.2 us per iteration at n = 8, d = 2^20; 9.5 against 9.1 us at n = 4, d = 1024).
  */
 int sgp_step(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
              float gamma, float momentum, int64_t k, void *stream);
