@@ -12,18 +12,22 @@
 // All floating-point code here is compiled without multiply-add contraction, so each operation
 // rounds separately, in the order written.
 //
-// Layout of the sources (one translation unit; the .inc files are included below):
-//   schedule.inc            host peer scheduler of the directed exponential graph
-//   device_common.inc       128-bit access helpers, local optimiser step, push-sum weight update
-//                           inside the step kernels, launch constants
-//   step_one_peer.inc       one out-peer: walk over the cycles of the shift
-//   step_stats_kernel.inc   the same walk with the consensus statistics taken from registers
-//   step_gather.inc         several out-peers / caller-supplied rows: private LDS columns
-//   step_complete.inc       complete graph
-//   step_overlap.inc        tau-overlap SGP: own share now, messages of the previous round
-//   debias_copy.inc         stand-alone de-bias, reference copy
-//   stats.inc               stand-alone consensus statistics and the final reductions
-//   sgp.hip                 handle, launchers, C ABI
+// Layout of the sources.  Several translation units, so that the kernel families compile side by side;
+// each includes internal.h and then the .inc files it needs inside an anonymous namespace:
+//   sgp.hip                       handle, host peer scheduler, C ABI, and the kernels of
+//     schedule.inc                  host peer scheduler of the directed exponential graph
+//     device_common.inc             128-bit access helpers, push-sum weight update inside the step
+//                                   kernels, local optimiser step (included by every unit)
+//     stats_tail.inc                end of every step kernel with fused statistics (every unit with one)
+//     step_one_peer.inc             one out-peer: walk over the cycles of the shift
+//     step_complete.inc             complete graph
+//     debias_copy.inc               stand-alone de-bias, reference copy
+//     stats.inc                     stand-alone consensus statistics and the final reductions
+//   sgp_walk_stats.hip            the one-peer walk with the consensus statistics taken from registers
+//                                 (step_walk_stats.inc); compiled once per variant of the kernel
+//   sgp_gather.hip                several out-peers / caller-supplied rows: private LDS columns (step_gather.inc)
+//   sgp_overlap.hip               tau-overlap SGP: own share now, messages of the previous round (step_overlap.inc)
+//   internal.h                    constants, kernel argument structures, launchers across the units
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
@@ -39,46 +43,19 @@
 #include <vector>
 
 #include "sgp.h"
+#include "internal.h"
 
 #pragma clang fp contract(off)
 
-// Tuning knobs (overridable at build time for tuning runs).
-// One-peer step kernel: single-wave blocks, one 128-bit column group per work-item measured best
-// (n = 32, d = 25.6 M: 3.05 ms; 256 x 4: 3.07 ms; 256 x 2: 3.17 ms).
-#ifndef SGP_OP_BLOCK
-#define SGP_OP_BLOCK 64
-#endif
-#ifndef SGP_OP_COLS
-#define SGP_OP_COLS 1
-#endif
-#ifndef SGP_DELAY_BLOCK
-#define SGP_DELAY_BLOCK 256
-#endif
-#ifndef SGP_DELAY_COLS
-#define SGP_DELAY_COLS 2
-#endif
-#ifndef SGP_DELAY_WINDOW
-#define SGP_DELAY_WINDOW 1   // two-peer overlap: walk with the stride of the two hops (0: table walk)
-#endif
-#ifndef SGP_NT_LOAD
-#define SGP_NT_LOAD 1
-#endif
-#ifndef SGP_NT_STORE
-#define SGP_NT_STORE 1
-#endif
+using namespace sgp_detail;
 
 namespace {
 
 #include "schedule.inc"
 #include "device_common.inc"
-
-constexpr int kStatsCache = 32;   // nodes whose z the small-n statistics kernels keep in registers
-
+#include "stats_tail.inc"
 #include "step_one_peer.inc"
-#include "step_stats_kernel.inc"
-#include "step_gather.inc"
 #include "step_complete.inc"
-#include "step_overlap.inc"
 #include "debias_copy.inc"
 #include "stats.inc"
 
@@ -254,8 +231,6 @@ int ensure_device(sgp_handle *h)
     return SGP_OK;
 }
 
-unsigned grid_for(long ncols, int block) { return (unsigned)((ncols + block - 1) / block); }
-
 // Whether a step with statistics can take them inside the step kernel (conditions common to every
 // kernel family; overlap mode additionally needs exactly two messages per receiver).
 bool fused_stats_applies(const sgp_handle *h, bool adam, bool vec, long tail)
@@ -322,19 +297,6 @@ void release_device(sgp_handle *h)
     }
 }
 
-struct StepArgs {
-    float *x, *u, *z;
-    const float *g;
-    WeightOp wop;
-    int n;
-    size_t ld;
-    float p;
-    Hyper hp;
-    hipStream_t stream;
-    const char **name;    // receives the name of the kernel launched
-    bool cached;          // small problem: ordinary loads and stores instead of streaming ones
-};
-
 template <int V, int OPT, bool ZOUT>
 void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
 {
@@ -347,38 +309,6 @@ void launch_one_peer(const StepArgs &a, size_t col0, long ncols, int h, int len)
                            dim3(kOpBlock), weight_lds_bytes(a.n), a.stream, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld,
                            col0, ncols, h, len, a.p, a.hp);
     *a.name = "k_step_one_peer";
-}
-
-// LDS of the gather kernel: the two weight arrays, then one private column of n values per work-item.
-size_t gather_lds_bytes(int n, int V) { return weight_lds_bytes(n) + (size_t)n * kGatherBlock * V * sizeof(float); }
-
-// fin != NULL: the launch carries the statistics (partial table `partial`) and `fin` is attached to
-// the kernel as its completion event.
-template <typename K, typename... Args>
-void launch_step(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t fin, Args... args)
-{
-    if (fin) hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, nullptr, fin, 0, args...);
-    else hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
-}
-
-template <int V, int OPT, bool ZOUT, bool STATS = false>
-void launch_gather(const StepArgs &a, size_t col0, long ncols, const int *tab, const float *tabw, int S,
-                   float *partial = nullptr, hipEvent_t fin = nullptr)
-{
-    const size_t lds = gather_lds_bytes(a.n, V);
-    dim3 grid(grid_for(ncols, kGatherBlock)), block(kGatherBlock);
-    auto go = [&](auto kernel) {
-        // more than 64 KiB of dynamic LDS has to be asked for per kernel (a failure shows up as the
-        // launch error that the caller checks)
-        if (lds > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        launch_step(kernel, grid, block, lds, a.stream, fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, col0, ncols,
-                    tab, tabw, S, a.p, a.hp, partial);
-    };
-    if (tabw) go(k_step_gather<V, OPT, ZOUT, true, STATS>);
-    else go(k_step_gather<V, OPT, ZOUT, false, STATS>);
-    *a.name = STATS ? "k_step_gather_stats" : "k_step_gather";
 }
 
 template <int V, int OPT, bool ZOUT, bool STATS = false>
@@ -395,65 +325,19 @@ void launch_complete(const StepArgs &a, size_t col0, long ncols, float *partial 
 void launch_walk_stats(const StepArgs &a, int opt, long cols4, int h, int len, float *partial, hipEvent_t fin,
                        const float *msg_prev = nullptr, float *msg_cur = nullptr, int ha = 0, int hb = 0)
 {
-    static_assert(kStatsStepBlock == kGatherBlock && kStatsStepBlock == kOpBlock,
-                  "every kernel with fused statistics writes one line of partial sums per 64 column groups");
-    auto go = [&](auto kernel) {
-        launch_step(kernel, dim3(grid_for(cols4, kStatsStepBlock)), dim3(kStatsStepBlock), weight_lds_bytes(a.n),
-                    a.stream, fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, cols4, h, len, a.p, a.hp, partial, msg_prev,
-                    msg_cur, ha, hb);
-    };
     const bool nest = opt == kOptNesterov;
+    auto go = [&]<bool CACHED, bool MSG>() {
+        if (nest) launch_walk_stats_variant<true, CACHED, MSG>(a, cols4, h, len, partial, fin, msg_prev, msg_cur, ha, hb);
+        else launch_walk_stats_variant<false, CACHED, MSG>(a, cols4, h, len, partial, fin, msg_prev, msg_cur, ha, hb);
+    };
     if (msg_prev) {
-        if (nest) go(k_step_one_peer_stats<true, false, true>);
-        else go(k_step_one_peer_stats<false, false, true>);
+        go.template operator()<false, true>();
         *a.name = "k_step_delay2_stats";
     } else {
-        if (nest) {
-            if (a.cached) go(k_step_one_peer_stats<true, true, false>);
-            else go(k_step_one_peer_stats<true, false, false>);
-        } else {
-            if (a.cached) go(k_step_one_peer_stats<false, true, false>);
-            else go(k_step_one_peer_stats<false, false, false>);
-        }
+        if (a.cached) go.template operator()<true, false>();
+        else go.template operator()<false, false>();
         *a.name = "k_step_one_peer_stats";
     }
-}
-
-template <int V, int OPT, bool ZOUT>
-void launch_delay(const StepArgs &a, size_t col0, long ncols, const float *msg_prev, float *msg_cur,
-                  const int *tab_prev, int S, int ha, int hb)
-{
-    dim3 grid(grid_for(ncols, kDelayBlock * kDelayCols)), block(kDelayBlock);
-    const size_t lds = weight_lds_bytes(a.n);
-    const int nm = tab_prev ? S - 1 : 0;
-    if (nm == 2 && SGP_DELAY_WINDOW) {   // two messages: each message row is loaded once
-        const int stride = ((hb - ha) % a.n + a.n) % a.n;
-        const int len = a.n / gcd_int(a.n, stride);
-        hipLaunchKernelGGL((k_step_delay2<V, OPT, ZOUT>), grid, block, lds, a.stream, a.x, a.u, a.g, a.z,
-                           a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, ha, hb, stride, len,
-                           a.p, a.hp);
-        *a.name = "k_step_delay2";
-        return;
-    }
-    *a.name = "k_step_delay";
-    if (nm == 0)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 0>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.hp);
-    else if (nm == 1)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 1>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.hp);
-#if !SGP_DELAY_WINDOW
-    else if (nm == 2)
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, 2>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.hp);
-#endif
-    else
-        hipLaunchKernelGGL((k_step_delay<V, OPT, ZOUT, -1>), grid, block, lds, a.stream, a.x, a.u, a.g,
-                           a.z, a.wop, msg_prev, msg_cur, a.n, a.ld, col0, ncols, tab_prev, S,
-                           a.p, a.hp);
 }
 
 // Calls f.template operator()<OPT, ZOUT>() for the run-time optimiser and z flag.
@@ -735,6 +619,9 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     // overlap mode: the fused walk exists for exactly two messages per receiver (two out-peers, and
     // something has been sent already)
     const bool two_msgs = h->delay != 0 && sending && h->have_msgs && h->L > 0 && S == 3;
+    // a problem whose arrays (x, u, g, z) all stay in the 256 MB last-level cache from one iteration to
+    // the next is better served by ordinary loads and stores than by streaming ones
+    const bool cached = (size_t)n * (size_t)h->ld * sizeof(float) * 4 <= kCachedStateBytes;
     const bool use_fused = fused && z_out && fused_stats_applies(h, adam != nullptr, cols4 > 0, tail) &&
                            (h->delay == 0 || !sending || two_msgs);
 
@@ -767,9 +654,6 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     wop.done = h->d_done;
     wop.hop = -1;
     const char *kname = "";
-    // a problem whose arrays (x, u, g, z) all stay in the 256 MB last-level cache from one iteration to
-    // the next is better served by ordinary loads and stores than by streaming ones
-    const bool cached = (size_t)n * (size_t)h->ld * sizeof(float) * 4 <= kCachedStateBytes;
     StepArgs a{x, m, z_out, g, wop, n, (size_t)h->ld, s.p, hp, st, &kname, cached};
     const int *tab_k = h->d_tab + (size_t)kmod * n * S;
     // a step is one launch over the 128-bit groups plus, for d % 4 != 0 or unaligned arrays, one over
@@ -837,14 +721,11 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         a.wop.tab = tab;
         a.wop.tabw = tabw;
         a.wop.S = entries;
-        if (use_fused) {
-            if (opt == kOptNesterov) launch_gather<4, kOptNesterov, true, true>(a, 0, cols4, tab, tabw, entries, partial, fin);
-            else launch_gather<4, kOptSgd, true, true>(a, 0, cols4, tab, tabw, entries, partial, fin);
-        } else
-        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
-            two_launches([&] { launch_gather<4, OPT, ZOUT>(a, 0, cols4, tab, tabw, entries); },
-                         [&] { launch_gather<1, OPT, ZOUT>(a, tail0, tail, tab, tabw, entries); });
-        });
+        const bool zo = z_out != nullptr;
+        if (use_fused) launch_gather(a, 4, opt, true, true, 0, cols4, tab, tabw, entries, partial, fin);
+        else
+            two_launches([&] { launch_gather(a, 4, opt, zo, false, 0, cols4, tab, tabw, entries, nullptr, nullptr); },
+                         [&] { launch_gather(a, 1, opt, zo, false, tail0, tail, tab, tabw, entries, nullptr, nullptr); });
     } else if (h->delay == 0) {
         const int hop = s.distinct ? s.uniq[0] % n : 0;
         const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
@@ -884,12 +765,12 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
             launch_walk_stats(a, opt, cols4, stride, len, partial, fin, h->d_msg[prv], h->d_msg[cur], ha, hb);
             fused->hop = stride;
             fused->len = len;
-        } else
-        dispatch_flags(opt, z_out != nullptr, [&]<int OPT, bool ZOUT>() {
+        } else {
+            const bool zo = z_out != nullptr;
             two_launches(
-                [&] { launch_delay<4, OPT, ZOUT>(a, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); },
-                [&] { launch_delay<1, OPT, ZOUT>(a, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); });
-        });
+                [&] { launch_delay(a, 4, opt, zo, 0, cols4, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); },
+                [&] { launch_delay(a, 1, opt, zo, tail0, tail, h->d_msg[prv], h->d_msg[cur], tab_prev, S, ha, hb); });
+        }
     }
     SGP_HIP_TRY(h, hipGetLastError());
     if (tev) {

@@ -65,6 +65,10 @@ WORKLOADS = {
                                       1e-3, 0.05),
     "x5_n16_resnet50_2peer": Workload("x5_n16_resnet50_2peer", 16, 25_557_032, 2, 0, 0.1, 0.9, 50, "fresh",
                                       1e-3, 0.05),
+    # a node count that is not a power of two (the exponential graph is then regular but a cycle of
+    # the schedule no longer averages exactly), with the statistics taken every step
+    "x6_n24_resnet50_stats": Workload("x6_n24_resnet50_stats", 24, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
+                                      1e-3, 0.05, stats_each_step=True),
     # storage experiment, not in the paper: configuration 4's shape (without the statistics) with g
     # and z, then also the momentum, held in memory as bfloat16; 20 and 16 bytes per node-parameter
     "h1_n32_resnet50_bf16_gz": Workload("h1_n32_resnet50_bf16_gz", 32, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",

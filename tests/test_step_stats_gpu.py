@@ -82,6 +82,18 @@ def test_fused_all_node_counts_and_hops(n):
     run(n, 2052, 2052, 1, 0, L + 1, 0.9, seed=n, spread=1.0, w_spread=True)
 
 
+@pytest.mark.parametrize("n,mom", [(3, 0.9), (6, 0.0), (11, 0.9), (14, 0.9), (19, 0.0), (23, 0.9), (27, 0.9),
+                                   (30, 0.0), (32, 0.9)])
+def test_fused_one_peer_streaming_accesses_any_node_count(n, mom):
+    """Problems above 160 MiB of state take the streaming instantiations of the walk (the small ones
+    above the cached ones): one count from every group of four that the kernel distinguishes, ragged
+    last block."""
+    ld = (((160 << 20) // (16 * n) + 64) + 3) // 4 * 4
+    d = ld - 8 - 4 * (n % 3)
+    run(n, d, ld, 1, 0, 2, mom, seed=100 + n, spread=0.1, w_spread=(n % 2 == 1), k0=n % 4,
+        kernels=["k_step_one_peer_stats"])
+
+
 @pytest.mark.parametrize("n", [3, 4, 5, 8, 13, 16, 32])
 def test_fused_two_peers_blocking(n):
     L = max(1, (n - 1).bit_length())
