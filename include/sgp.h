@@ -430,6 +430,18 @@ int sgp_placer_take(sgp_placer *p, int32_t role, int64_t nbytes, int64_t *offset
  * hardware traffic counters are scaled, and as the practical bandwidth ceiling of the part. */
 int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
+/* Measurement utility: one launch, on `stream`, of a structure-free kernel that reads each of
+ * n_reads arrays and writes each of n_writes arrays of nbytes once, with 128-bit streaming
+ * accesses: the traffic of a step kernel (3 reads and 3 writes per node-parameter) without its walk,
+ * for any choice of where the arrays lie and of which are updated in place.  Every written element
+ * is the float sum of the elements read at its offset (zero without reads).
+ * reads, writes: HOST arrays of n_reads / n_writes DEVICE pointers, 16-byte aligned; 0..4 of each
+ * and at least one in total; nbytes a multiple of 16.  A written array may coincide with a read
+ * array (in place); apart from that no two arrays may overlap (SGP_ERR_INVALID_ARG).  Nothing is
+ * allocated; the caller times the launch. */
+int sgp_stream_pattern(const void *const *reads, int32_t n_reads, void *const *writes, int32_t n_writes,
+                       int64_t nbytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -37,7 +37,8 @@ EXPORTS = ("sgp_create", "sgp_destroy", "sgp_reset", "sgp_step", "sgp_debias",
            "sgp_pregossip_stats", "sgp_step_stats_begin", "sgp_step_stats_end",
            "sgp_consensus_stats_noalloc", "sgp_last_step_kernel", "sgp_probe_regions",
            "sgp_smooth_region_classes", "sgp_step_bf16", "sgp_debug_fail_alloc",
-           "sgp_placer_create", "sgp_placer_destroy", "sgp_placer_reset", "sgp_placer_take")
+           "sgp_placer_create", "sgp_placer_destroy", "sgp_placer_reset", "sgp_placer_take",
+           "sgp_stream_pattern")
 
 
 class SgpError(RuntimeError):
@@ -93,6 +94,7 @@ def load_library() -> ctypes.CDLL:
     lib.sgp_status_string.restype = ctypes.c_char_p
     lib.sgp_last_hip_error.argtypes = [vp]
     lib.sgp_copy.argtypes = [vp, vp, i64, vp]
+    lib.sgp_stream_pattern.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, i64, vp]
     lib.sgp_set_message_buffers.argtypes = [vp, vp, vp]
     lib.sgp_step_stats.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, i64, ctypes.POINTER(_CStats), vp, vp]
     lib.sgp_set_biased.argtypes = [vp, ctypes.c_int]
@@ -159,6 +161,18 @@ def sgp_copy(dst, src, nbytes: Optional[int] = None, stream=None) -> None:
     if nbytes is None:
         nbytes = src.numel() * src.element_size()
     _check(load_library().sgp_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "sgp_copy")
+
+
+def sgp_stream_pattern(reads, writes, nbytes: Optional[int] = None, stream=None) -> None:
+    """One launch of the structure-free stream kernel: reads every tensor of `reads`, writes every
+    tensor of `writes` (see include/sgp.h); all of the same size."""
+    both = list(reads) + list(writes)
+    if nbytes is None:
+        nbytes = both[0].numel() * both[0].element_size() if both else 0
+    r = (ctypes.c_void_p * max(1, len(reads)))(*[_ptr(t) for t in reads])
+    w = (ctypes.c_void_p * max(1, len(writes)))(*[_ptr(t) for t in writes])
+    _check(load_library().sgp_stream_pattern(r, len(reads), w, len(writes), nbytes, _stream(stream)),
+           "sgp_stream_pattern")
 
 
 def sgp_consensus_stats_noalloc(n: int, d: int, ld: int, z, w, out_device, stream=None) -> None:

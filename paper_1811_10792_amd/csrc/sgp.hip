@@ -1419,4 +1419,40 @@ int sgp_copy(void *dst, const void *src, int64_t nbytes, void *stream)
     return SGP_OK;
 }
 
+int sgp_stream_pattern(const void *const *reads, int32_t n_reads, void *const *writes, int32_t n_writes,
+                       int64_t nbytes, void *stream)
+{
+    if (n_reads < 0 || n_reads > kPatternMax || n_writes < 0 || n_writes > kPatternMax || n_reads + n_writes == 0 ||
+        nbytes < 0 || (nbytes & 15) || (n_reads && !reads) || (n_writes && !writes))
+        return SGP_ERR_INVALID_ARG;
+    PatternPtrs p{};
+    for (int j = 0; j < n_reads; ++j) {
+        if (!reads[j] || !aligned16(reads[j])) return SGP_ERR_INVALID_ARG;
+        p.r[j] = static_cast<const floatx4 *>(reads[j]);
+    }
+    for (int j = 0; j < n_writes; ++j) {
+        if (!writes[j] || !aligned16(writes[j])) return SGP_ERR_INVALID_ARG;
+        p.w[j] = static_cast<floatx4 *>(writes[j]);
+    }
+    // arrays may coincide (a written array that is also read: in place) but not overlap otherwise
+    auto overlap_ok = [&](const void *a, const void *b) {
+        const char *ca = static_cast<const char *>(a), *cb = static_cast<const char *>(b);
+        return ca == cb || ca + nbytes <= cb || cb + nbytes <= ca;
+    };
+    for (int j = 0; j < n_writes; ++j) {
+        for (int q = 0; q < n_reads; ++q)
+            if (!overlap_ok(writes[j], reads[q])) return SGP_ERR_INVALID_ARG;
+        for (int q = 0; q < j; ++q)
+            if (writes[q] == writes[j] || !overlap_ok(writes[j], writes[q])) return SGP_ERR_INVALID_ARG;
+    }
+    if (nbytes == 0) return SGP_OK;
+    const size_t count = (size_t)nbytes / 16;
+    const size_t blocks = (count + kBlock - 1) / kBlock;
+    if (blocks > 0x7fffffffu) return SGP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_stream_pattern, dim3((unsigned)blocks), dim3(kBlock), 0, static_cast<hipStream_t>(stream), p,
+                       n_reads, n_writes, count);
+    if (hipGetLastError() != hipSuccess) return SGP_ERR_HIP;
+    return SGP_OK;
+}
+
 }  // extern "C"

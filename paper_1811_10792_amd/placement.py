@@ -210,5 +210,104 @@ def _report() -> None:
     eng.close()
 
 
+def _patterns() -> None:
+    """Where could the six streams of a step lie?  (python -m paper_1811_10792_amd.placement --patterns)
+    Times the structure-free stream kernel (sgp_stream_pattern: 3 reads x, u, g and 3 writes x', u', z
+    of the benchmark's array size) for every assignment of the six streams to the three regions,
+    out of place (x', u' are other arrays than x, u) and in place (x' = x, u' = u), and looks for the
+    best schedule that repeats: an iteration must read x and u where the one before wrote them."""
+    import itertools
+    import torch
+    from .binding import sgp_stream_pattern
+    from . import synthetic as syn
+    torch.cuda.set_device(0)
+    placer, regions = make_placer()
+    if placer is None or not regions.structured:
+        print("no arena, or no region structure found")
+        return
+    arena, g = placer.arena, regions.granule
+    runs = {c: max(regions.runs(c), key=lambda r: r[1]) for c in set(regions.classes) if c >= 0}
+    if len(runs) < 3:
+        print("fewer than three regions found")
+        return
+    n, d = 32, 25_557_032
+    ld = syn.padded_ld(d)
+    arr = n * ld * 4
+    a = (arr + 4095) // 4096 * 4096
+    print("region of each granule (granule %d GiB): %s" % (g // GIB, "".join(str(c) for c in regions.classes)))
+    print("arrays of %d bytes (n = 32, d = 25,557,032); stream k of a pattern uses slot k of its region" % arr)
+    # six slots in every region, from its second granule on
+    slot = {}
+    for c in (0, 1, 2):
+        first, count = runs[c]
+        if (count - 1) * g < 6 * a:
+            print("region %d too small" % c)
+            return
+        for k in range(6):
+            slot[c, k] = arena.floats((first + 1) * g + k * a, n, ld)
+            slot[c, k].zero_()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def time_ms(reads, writes):
+        sgp_stream_pattern(reads, writes)
+        ms = []
+        for _ in range(3):
+            e0.record()
+            sgp_stream_pattern(reads, writes)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return sorted(ms)[1]
+
+    def tbs(ms):
+        return 6 * arr / ms / 1e9
+
+    oop = {}
+    for pat in itertools.product((0, 1, 2), repeat=6):            # rx ru rg wx wu wz
+        reads = [slot[pat[k], k] for k in range(3)]
+        writes = [slot[pat[k], k] for k in range(3, 6)]
+        oop[pat] = time_ms(reads, writes)
+    inp = {}
+    for pat in itertools.product((0, 1, 2), repeat=4):            # rx ru rg wz, x and u written where they are read
+        reads = [slot[pat[k], k] for k in range(3)]
+        inp[pat] = time_ms(reads, [reads[0], reads[1], slot[pat[3], 5]])
+
+    def show(tag, table, key):
+        print("  %-44s %s   %.3f ms  %.2f TB/s" % (tag, "".join(map(str, key)), table[key], tbs(table[key])))
+    print("in place (regions of x u g z):")
+    show("the library's placement (x, g | u | z)", inp, (0, 1, 0, 2))
+    show("best", inp, min(inp, key=inp.get))
+    show("worst", inp, max(inp, key=inp.get))
+    print("out of place (regions of x u g x' u' z):")
+    for key in sorted(oop, key=oop.get)[:8]:
+        show("one of the eight best", oop, key)
+    show("worst", oop, max(oop, key=oop.get))
+    print("  rotation: read region k, write x', u' to region k+1 and z to region k+2 (and the other way round):")
+    for sign in (1, 2):
+        tot = 0.0
+        for k in (0, 1, 2):
+            key = (k, k, k, (k + sign) % 3, (k + sign) % 3, (k + 2 * sign) % 3)
+            show("phase %d" % k, oop, key)
+            tot += oop[key]
+        print("  %-44s          %.3f ms  %.2f TB/s" % ("average over the rotation", tot / 3, tbs(tot / 3)))
+    # schedules that repeat: state = (region of x, region of u); an iteration moves the state to
+    # (region of x', region of u'), g and z lie wherever is best for that iteration
+    states = list(itertools.product((0, 1, 2), repeat=2))
+    cost = {(s, t): min(oop[s + (rg,) + t + (wz,)] for rg in (0, 1, 2) for wz in (0, 1, 2)) for s in states for t in states}
+    best = (float("inf"), None)
+    for length in (1, 2, 3, 4):
+        for cyc in itertools.product(states, repeat=length):
+            mean = sum(cost[cyc[i], cyc[(i + 1) % length]] for i in range(length)) / length
+            if mean < best[0] - 1e-9:
+                best = (mean, cyc)
+    print("best repeating out-of-place schedule (period <= 4), states (region of x, region of u): %s" % (best[1],))
+    print("  mean %.3f ms per iteration = %.2f TB/s; in place at the library's placement: %.3f ms = %.2f TB/s"
+          % (best[0], tbs(best[0]), inp[0, 1, 0, 2], tbs(inp[0, 1, 0, 2])))
+
+
 if __name__ == "__main__":
-    _report()
+    import sys
+    if "--patterns" in sys.argv[1:]:
+        _patterns()
+    else:
+        _report()

@@ -68,6 +68,27 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.sgp_destroy(h) == 0
 
 
+def test_stream_pattern_argument_checks(lib):
+    """All of these are refused before anything is launched (the addresses are never touched)."""
+    vp = ctypes.c_void_p
+
+    def call(reads, writes, nbytes):
+        r = (vp * max(1, len(reads)))(*reads)
+        w = (vp * max(1, len(writes)))(*writes)
+        return lib.sgp_stream_pattern(r, len(reads), w, len(writes), nbytes, None)
+    bad = binding.SGP_ERR_INVALID_ARG
+    assert call([], [], 1024) == bad                                   # nothing to do
+    assert call([4096] * 5, [], 1024) == bad                           # more than four of a kind
+    assert call([4096], [8192], 1000) == bad                           # not a multiple of 16
+    assert call([4096], [8200], 1024) == bad                           # misaligned
+    assert call([4096], [None], 1024) == bad
+    assert call([4096], [4096 + 512], 1024) == bad                     # partial overlap of a read and a write
+    assert call([4096], [16384, 16384], 1024) == bad                   # the same array written twice
+    assert call([4096], [16384, 16384 + 512], 1024) == bad             # overlapping writes
+    assert call([4096], [4096], 0) == 0                                # in place is fine; empty: nothing launched
+    assert lib.sgp_stream_pattern(None, 1, None, 0, 1024, None) == bad
+
+
 @pytest.mark.parametrize("peers", [1, 2, 3])
 def test_schedule_matches_oracle_nonzeros_exactly(lib, peers):
     for n in list(range(1, 18)) + [31, 32, 33, 64, 100]:
