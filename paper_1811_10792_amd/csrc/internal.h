@@ -41,6 +41,9 @@
 #ifndef SGP_STATS_DEPTH
 #define SGP_STATS_DEPTH 4
 #endif
+#ifndef SGP_STATS_EXACT
+#define SGP_STATS_EXACT 1    // walk with statistics: bodies with the node count known exactly for 4, 8, 16, 32
+#endif
 #ifndef SGP_H16_COLS
 #define SGP_H16_COLS 1
 #endif

@@ -34,9 +34,23 @@ void launch_walk_stats_variant<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), (SG
     const StepArgs &a, long cols4, int h, int len, float *partial, hipEvent_t fin, const float *msg_prev,
     float *msg_cur, int ha, int hb)
 {
-    launch_step(k_step_one_peer_stats<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), (SGP_WALK_MSG != 0)>,
-                dim3(grid_for(cols4, kStatsStepBlock)), dim3(kStatsStepBlock), weight_lds_bytes(a.n), a.stream, fin,
-                a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, cols4, h, len, a.p, a.hp, partial, msg_prev, msg_cur, ha, hb);
+    auto go = [&]<int NB>() {
+        launch_step(k_step_one_peer_stats<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), (SGP_WALK_MSG != 0), NB>,
+                    dim3(grid_for(cols4, kStatsStepBlock)), dim3(kStatsStepBlock), weight_lds_bytes(a.n), a.stream,
+                    fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, cols4, h, len, a.p, a.hp, partial, msg_prev, msg_cur,
+                    ha, hb);
+    };
+    switch ((a.n + 3) / 4) {     // one kernel per group of four node counts
+    case 0:
+    case 1: go.template operator()<4>(); break;
+    case 2: go.template operator()<8>(); break;
+    case 3: go.template operator()<12>(); break;
+    case 4: go.template operator()<16>(); break;
+    case 5: go.template operator()<20>(); break;
+    case 6: go.template operator()<24>(); break;
+    case 7: go.template operator()<28>(); break;
+    default: go.template operator()<32>(); break;
+    }
 }
 
 }  // namespace sgp_detail
