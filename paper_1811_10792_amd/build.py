@@ -24,7 +24,8 @@ UNITS = [
     _walk(1, 0, 1), _walk(0, 0, 1), _walk(1, 0, 0), _walk(1, 1, 0), _walk(0, 0, 0), _walk(0, 1, 0),
     ("sgp.hip", "sgp", []),
     ("sgp_overlap.hip", "sgp_overlap", []),
-    ("sgp_gather.hip", "sgp_gather", []),
+    ("sgp_gather.hip", "sgp_gather", ["-DSGP_GATHER_STATS=0"]),
+    ("sgp_gather.hip", "sgp_gather_stats", ["-DSGP_GATHER_STATS=1"]),
 ]
 
 HIPCC_FLAGS = [

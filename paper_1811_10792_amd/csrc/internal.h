@@ -191,10 +191,13 @@ SGP_DECLARE_WALK_STATS(false, false, true)
 SGP_DECLARE_WALK_STATS(true, false, true)
 #undef SGP_DECLARE_WALK_STATS
 
-// sgp_gather.hip: several out-peers or caller-supplied rows (tabw != NULL), through private LDS
-// columns; stats: with the consensus statistics (V = 4, z written, partial and fin given).
-void launch_gather(const StepArgs &a, int V, int opt, bool zout, bool stats, size_t col0, long ncols, const int *tab,
-                   const float *tabw, int S, float *partial, hipEvent_t fin);
+// sgp_gather.hip (compiled twice, without and with the statistics): several out-peers or
+// caller-supplied rows (tabw != NULL), through private LDS columns.  With statistics: Alg. 1 or
+// Alg. 3 only, 128-bit layout from column 0, z written, n <= kStatsCache.
+void launch_gather(const StepArgs &a, int V, int opt, bool zout, size_t col0, long ncols, const int *tab,
+                   const float *tabw, int S);
+void launch_gather_stats(const StepArgs &a, int opt, long ncols, const int *tab, const float *tabw, int S,
+                         float *partial, hipEvent_t fin);
 
 // sgp_overlap.hip: one iteration of delay; tab_prev == NULL: nothing in flight yet.
 void launch_delay(const StepArgs &a, int V, int opt, bool zout, size_t col0, long ncols, const float *msg_prev,

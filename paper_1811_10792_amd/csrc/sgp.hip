@@ -25,7 +25,8 @@
 //     stats.inc                     stand-alone consensus statistics and the final reductions
 //   sgp_walk_stats.hip            the one-peer walk with the consensus statistics taken from registers
 //                                 (step_walk_stats.inc); compiled once per variant of the kernel
-//   sgp_gather.hip                several out-peers / caller-supplied rows: private LDS columns (step_gather.inc)
+//   sgp_gather.hip                several out-peers / caller-supplied rows: private LDS columns (step_gather.inc);
+//                                 compiled twice, without and with the statistics
 //   sgp_overlap.hip               tau-overlap SGP: own share now, messages of the previous round (step_overlap.inc)
 //   internal.h                    constants, kernel argument structures, launchers across the units
 #include <hip/hip_runtime.h>
@@ -722,10 +723,10 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         a.wop.tabw = tabw;
         a.wop.S = entries;
         const bool zo = z_out != nullptr;
-        if (use_fused) launch_gather(a, 4, opt, true, true, 0, cols4, tab, tabw, entries, partial, fin);
+        if (use_fused) launch_gather_stats(a, opt, cols4, tab, tabw, entries, partial, fin);
         else
-            two_launches([&] { launch_gather(a, 4, opt, zo, false, 0, cols4, tab, tabw, entries, nullptr, nullptr); },
-                         [&] { launch_gather(a, 1, opt, zo, false, tail0, tail, tab, tabw, entries, nullptr, nullptr); });
+            two_launches([&] { launch_gather(a, 4, opt, zo, 0, cols4, tab, tabw, entries); },
+                         [&] { launch_gather(a, 1, opt, zo, tail0, tail, tab, tabw, entries); });
     } else if (h->delay == 0) {
         const int hop = s.distinct ? s.uniq[0] % n : 0;
         const int ncyc = s.distinct ? gcd_int(n, hop) : n;   // no peer: n cycles of length 1
