@@ -402,8 +402,8 @@ int sgp_smooth_region_classes(int32_t *class_of_granule, int32_t count);
  *   sgp_placer_take   : a fresh range of nbytes for an array in the given role.  Roles: x, u (the
  *                       array `m` of sgp_step) and z are the three written streams and go to three
  *                       different regions, the largest regions first; g is read-only and shares the
- *                       region of x; the two message buffers of overlap mode go with u and with x;
- *                       Adam's second moment with z.  Inside a region the interiors of long runs of
+ *                       region of x; the two message buffers of overlap mode go with u;
+ *                       Adam's second moment with x.  Inside a region the interiors of long runs of
  *                       granules are used before their edge granules (which may straddle a region
  *                       boundary) and before short runs.  When the preferred region is full, any
  *                       other with room is taken; *class_out (nullable) tells which region it was.

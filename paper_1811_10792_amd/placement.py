@@ -110,8 +110,9 @@ class StateAllocator:
     """Allocates the [n, ld] float32 state arrays of one SGP problem, region-aware when an arena
     could be set up and plainly otherwise.  Roles: "x", "u", "z" are the three written streams and
     go to three different regions; "g" buffers are read-only and share the region of x; the
-    message buffers of overlap mode go with u ("msg0") and with x ("msg1"): a message buffer written
-    into the region of z measured 2.5 % slower (17.5 against 17.1 ms at n = 16, d = 213 M)."""
+    message buffers of overlap mode ("msg0", "msg1") go with u: a message buffer written into the
+    region of z measured 2.5 % slower (17.5 against 17.1 ms at n = 16, d = 213 M); Adam's second
+    moment ("v") goes with x."""
 
     def __init__(self, mode: str = "regions", device="cuda"):
         self.device = device

@@ -91,7 +91,7 @@ def test_roles_share_and_separate_regions_as_documented():
     p = Placer(FakeArena(len(classes) * 8 * GIB), _map(classes))
     arr = (16, 213_000_192)                                      # 13.6 GB each
     cls = {role: p.floats(*arr, role)[1] for role in ("x", "g", "u", "z", "msg0", "msg1", "v")}
-    assert cls["g"] == cls["x"] == cls["msg1"] and cls["msg0"] == cls["u"] and cls["v"] == cls["z"]
+    assert cls["g"] == cls["x"] == cls["v"] and cls["msg0"] == cls["msg1"] == cls["u"]
     assert len({cls["x"], cls["u"], cls["z"]}) == 3
 
 
