@@ -266,9 +266,9 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
  * host_out are required.  With n <= 32, d % 4 == 0, the 128-bit layout and SGD or Nesterov as the
  * local step, the statistics are accumulated inside the step kernel while z is still in registers
  * (z is not read back from HBM), for every topology without delay, for the iterations between two
- * communication rounds of tau-overlap SGP, and for overlap iterations that receive exactly two
- * messages per node (two out-peers; the very first iteration, which receives nothing, does not
- * qualify); otherwise the two kernels run one after the other.  The state written is identical to
+ * communication rounds of tau-overlap SGP, and for overlap iterations that receive one or two
+ * messages per node (one or two out-peers; the very first iteration, which receives nothing, does
+ * not qualify); otherwise the two kernels run one after the other.  The state written is identical to
  * sgp_step's; the statistics agree with sgp_consensus_stats to rounding (a different reference row
  * is subtracted before squaring).  The reduction of the fused kernel's partial sums runs on a stream
  * that the library owns, behind the step kernel.  SYNCHRONISES the stream.
@@ -346,8 +346,8 @@ int sgp_debug_fail_alloc(int32_t succeed_first);
 /* Measurement utility: static name of the step kernel that the latest successful step on this
  * handle launched ("k_step_one_peer", "k_step_gather", "k_step_complete", "k_step_delay",
  * "k_step_delay2", "k_step_one_peer_h16", and with fused statistics "k_step_one_peer_stats",
- * "k_step_gather_stats", "k_step_complete_stats", "k_step_delay2_stats"; "" before the first step), so that a benchmark can report what
- * ran instead of re-deriving the library's dispatch. */
+ * "k_step_gather_stats", "k_step_complete_stats", "k_step_delay1_stats", "k_step_delay2_stats";
+ * "" before the first step), so that a benchmark can report what ran instead of re-deriving the library's dispatch. */
 const char *sgp_last_step_kernel(const sgp_handle *h);
 
 /*

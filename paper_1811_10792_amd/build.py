@@ -21,7 +21,8 @@ def _walk(nest: int, cached: int, msg: int):
 
 
 UNITS = [
-    _walk(1, 0, 1), _walk(0, 0, 1), _walk(1, 0, 0), _walk(1, 1, 0), _walk(0, 0, 0), _walk(0, 1, 0),
+    _walk(1, 0, 2), _walk(0, 0, 2), _walk(1, 0, 1), _walk(0, 0, 1), _walk(1, 0, 0), _walk(1, 1, 0), _walk(0, 0, 0),
+    _walk(0, 1, 0),
     ("sgp.hip", "sgp", []),
     ("sgp_overlap.hip", "sgp_overlap", []),
     ("sgp_gather.hip", "sgp_gather", ["-DSGP_GATHER_STATS=0"]),

@@ -172,10 +172,11 @@ void launch_step(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hi
 // ------------------------------------------------------------------------------------------
 
 // sgp_walk_stats.hip, compiled once per variant: the unrolled walk with the statistics taken from
-// registers, for any n <= kStatsCache: one out-peer (or none), or, MSG, two out-peers under one
-// iteration of delay (msg_prev, msg_cur, ha, hb; otherwise unused).  The variants that exist are
-// declared here; MSG has no CACHED form.
-template <bool NEST, bool CACHED, bool MSG>
+// registers, for any n <= kStatsCache: one out-peer (or none) without delay (MSG = 0), or one
+// iteration of delay with MSG = 1 or 2 out-peers (msg_prev, msg_cur, the previous round's hops ha
+// and, MSG = 2, hb; otherwise unused).  The variants that exist are declared here; MSG != 0 has no
+// CACHED form.
+template <bool NEST, bool CACHED, int MSG>
 void launch_walk_stats_variant(const StepArgs &a, long cols4, int h, int len, float *partial, hipEvent_t fin,
                                const float *msg_prev, float *msg_cur, int ha, int hb);
 #define SGP_DECLARE_WALK_STATS(NEST, CACHED, MSG)                                                              \
@@ -183,12 +184,14 @@ void launch_walk_stats_variant(const StepArgs &a, long cols4, int h, int len, fl
     void launch_walk_stats_variant<NEST, CACHED, MSG>(const StepArgs &a, long cols4, int h, int len,          \
                                                       float *partial, hipEvent_t fin, const float *msg_prev,  \
                                                       float *msg_cur, int ha, int hb);
-SGP_DECLARE_WALK_STATS(false, false, false)
-SGP_DECLARE_WALK_STATS(true, false, false)
-SGP_DECLARE_WALK_STATS(false, true, false)
-SGP_DECLARE_WALK_STATS(true, true, false)
-SGP_DECLARE_WALK_STATS(false, false, true)
-SGP_DECLARE_WALK_STATS(true, false, true)
+SGP_DECLARE_WALK_STATS(false, false, 0)
+SGP_DECLARE_WALK_STATS(true, false, 0)
+SGP_DECLARE_WALK_STATS(false, true, 0)
+SGP_DECLARE_WALK_STATS(true, true, 0)
+SGP_DECLARE_WALK_STATS(false, false, 1)
+SGP_DECLARE_WALK_STATS(true, false, 1)
+SGP_DECLARE_WALK_STATS(false, false, 2)
+SGP_DECLARE_WALK_STATS(true, false, 2)
 #undef SGP_DECLARE_WALK_STATS
 
 // sgp_gather.hip (compiled twice, without and with the statistics): several out-peers or

@@ -321,22 +321,25 @@ void launch_complete(const StepArgs &a, size_t col0, long ncols, float *partial 
     *a.name = STATS ? "k_step_complete_stats" : "k_step_complete";
 }
 
-// The unrolled walk with the statistics taken from registers: one out-peer (or none), or, with
-// msg_prev != NULL, two out-peers under one iteration of delay.
+// The unrolled walk with the statistics taken from registers: one out-peer (or none) without delay
+// (msgs = 0), or one iteration of delay with msgs = 1 or 2 messages per receiver.
 void launch_walk_stats(const StepArgs &a, int opt, long cols4, int h, int len, float *partial, hipEvent_t fin,
-                       const float *msg_prev = nullptr, float *msg_cur = nullptr, int ha = 0, int hb = 0)
+                       int msgs = 0, const float *msg_prev = nullptr, float *msg_cur = nullptr, int ha = 0, int hb = 0)
 {
     const bool nest = opt == kOptNesterov;
-    auto go = [&]<bool CACHED, bool MSG>() {
+    auto go = [&]<bool CACHED, int MSG>() {
         if (nest) launch_walk_stats_variant<true, CACHED, MSG>(a, cols4, h, len, partial, fin, msg_prev, msg_cur, ha, hb);
         else launch_walk_stats_variant<false, CACHED, MSG>(a, cols4, h, len, partial, fin, msg_prev, msg_cur, ha, hb);
     };
-    if (msg_prev) {
-        go.template operator()<false, true>();
+    if (msgs == 2) {
+        go.template operator()<false, 2>();
         *a.name = "k_step_delay2_stats";
+    } else if (msgs == 1) {
+        go.template operator()<false, 1>();
+        *a.name = "k_step_delay1_stats";
     } else {
-        if (a.cached) go.template operator()<true, false>();
-        else go.template operator()<false, false>();
+        if (a.cached) go.template operator()<true, 0>();
+        else go.template operator()<false, 0>();
         *a.name = "k_step_one_peer_stats";
     }
 }
@@ -617,14 +620,15 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     const long cols4 = vec ? (long)(h->d / 4) : 0;             // full 128-bit groups
     const size_t tail0 = (size_t)cols4 * 4;
     const long tail = (long)(h->d - (int64_t)tail0);           // scalar columns after them
-    // overlap mode: the fused walk exists for exactly two messages per receiver (two out-peers, and
-    // something has been sent already)
+    // overlap mode: the fused walk exists for one and for two messages per receiver (one or two
+    // distinct out-peers, and something has been sent already)
     const bool two_msgs = h->delay != 0 && sending && h->have_msgs && h->L > 0 && S == 3;
+    const bool one_msg = h->delay != 0 && sending && h->have_msgs && h->L > 0 && S == 2;
     // a problem whose arrays (x, u, g, z) all stay in the 256 MB last-level cache from one iteration to
     // the next is better served by ordinary loads and stores than by streaming ones
     const bool cached = (size_t)n * (size_t)h->ld * sizeof(float) * 4 <= kCachedStateBytes;
     const bool use_fused = fused && z_out && fused_stats_applies(h, adam != nullptr, cols4 > 0, tail) &&
-                           (h->delay == 0 || !sending || two_msgs);
+                           (h->delay == 0 || !sending || two_msgs || one_msg);
 
     int rc = ensure_device(h);
     if (rc != SGP_OK) return rc;
@@ -745,10 +749,10 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     } else {
         const int *tab_prev = nullptr;
         int ha = 0, hb = 0;          // the previous round's hops, when there are exactly two
-        if (h->have_msgs && h->L > 0 && S == 3) {
+        if (h->have_msgs && h->L > 0 && (S == 3 || S == 2)) {
             const Schedule sp = make_schedule(n, h->peers, round - 1);
             ha = sp.uniq[0] % n;
-            hb = sp.uniq[1] % n;
+            if (S == 3) hb = sp.uniq[1] % n;
         }
         if (h->have_msgs && h->L > 0) {
             const int kprev = (int)((round - 1) % h->L);
@@ -760,10 +764,14 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
         a.wop.S = S;
         a.wop.msgw_prev = h->d_msgw[prv];
         a.wop.msgw_cur = h->d_msgw[cur];
-        if (use_fused) {             // two messages per receiver: the stride walk of k_step_delay2
+        if (use_fused && one_msg) {  // one message per receiver: rows are independent, cycles of one node
+            launch_walk_stats(a, opt, cols4, 0, 1, partial, fin, 1, h->d_msg[prv], h->d_msg[cur], ha, 0);
+            fused->hop = 0;
+            fused->len = 1;
+        } else if (use_fused) {      // two messages per receiver: the stride walk of k_step_delay2
             const int stride = ((hb - ha) % n + n) % n;
             const int len = n / gcd_int(n, stride);
-            launch_walk_stats(a, opt, cols4, stride, len, partial, fin, h->d_msg[prv], h->d_msg[cur], ha, hb);
+            launch_walk_stats(a, opt, cols4, stride, len, partial, fin, 2, h->d_msg[prv], h->d_msg[cur], ha, hb);
             fused->hop = stride;
             fused->len = len;
         } else {

@@ -3,7 +3,7 @@
 // minute to compile, so this file is compiled once per variant, side by side, with
 //   -DSGP_WALK_NEST=0|1    local optimiser: gradient step / Nesterov momentum
 //   -DSGP_WALK_CACHED=0|1  streaming / ordinary loads and stores
-//   -DSGP_WALK_MSG=0|1     two out-peers under one iteration of delay (never together with CACHED)
+//   -DSGP_WALK_MSG=0|1|2   one iteration of delay with one / two out-peers (never together with CACHED)
 // and each object defines the launcher of its variant.
 #include "internal.h"
 
@@ -30,12 +30,12 @@ namespace {
 namespace sgp_detail {
 
 template <>
-void launch_walk_stats_variant<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), (SGP_WALK_MSG != 0)>(
+void launch_walk_stats_variant<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), SGP_WALK_MSG>(
     const StepArgs &a, long cols4, int h, int len, float *partial, hipEvent_t fin, const float *msg_prev,
     float *msg_cur, int ha, int hb)
 {
     auto go = [&]<int NB>() {
-        launch_step(k_step_one_peer_stats<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), (SGP_WALK_MSG != 0), NB>,
+        launch_step(k_step_one_peer_stats<(SGP_WALK_NEST != 0), (SGP_WALK_CACHED != 0), SGP_WALK_MSG, NB>,
                     dim3(grid_for(cols4, kStatsStepBlock)), dim3(kStatsStepBlock), weight_lds_bytes(a.n), a.stream,
                     fin, a.x, a.u, a.g, a.z, a.wop, a.n, a.ld, cols4, h, len, a.p, a.hp, partial, msg_prev, msg_cur,
                     ha, hb);

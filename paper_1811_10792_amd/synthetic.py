@@ -69,6 +69,10 @@ WORKLOADS = {
     # the schedule no longer averages exactly), with the statistics taken every step
     "x6_n24_resnet50_stats": Workload("x6_n24_resnet50_stats", 24, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",
                                       1e-3, 0.05, stats_each_step=True),
+    # the paper's 1-peer overlap runs on ResNet-50 (one out-peer, one iteration of delay) on
+    # configuration 4's shape, with the statistics taken every step
+    "x7_n32_resnet50_overlap_stats": Workload("x7_n32_resnet50_overlap_stats", 32, 25_557_032, 1, 1, 0.1, 0.9, 50,
+                                              "fresh", 1e-3, 0.05, stats_each_step=True),
     # storage experiment, not in the paper: configuration 4's shape (without the statistics) with g
     # and z, then also the momentum, held in memory as bfloat16; 20 and 16 bytes per node-parameter
     "h1_n32_resnet50_bf16_gz": Workload("h1_n32_resnet50_bf16_gz", 32, 25_557_032, 1, 0, 0.1, 0.9, 50, "fresh",

@@ -20,6 +20,7 @@ def test_algorithmic_bytes_per_update():
             "x2_n32_resnet50_complete": 24.0,
             "x3_n16_transformer_2peer_overlap_adam": 40.0,       # + second moment read and written
             "x4_n32_resnet50_2peer": 24.0, "x5_n16_resnet50_2peer": 24.0, "x6_n24_resnet50_stats": 24.0,
+            "x7_n32_resnet50_overlap_stats": 32.0,            # + message read and written
             "h1_n32_resnet50_bf16_gz": 20.0, "h2_n32_resnet50_bf16_guz": 16.0}   # storage experiment
     assert set(want) == set(syn.WORKLOADS)
     for name, b in want.items():

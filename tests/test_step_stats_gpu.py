@@ -117,10 +117,22 @@ def test_fused_complete_graph(n):
         kernels=["k_step_complete_stats"])
 
 
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 8, 13, 16, 27, 32])
+def test_fused_one_peer_one_iteration_of_delay(n):
+    """One out-peer under one iteration of delay: the first iteration has nothing to receive (table-driven
+    kernel plus a statistics pass); from then on every row adds its one message and the statistics
+    come from registers."""
+    L = max(1, (n - 1).bit_length())
+    run(n, 2052, 2052, 1, 1, L + 3, 0.9, seed=n, spread=1.0, w_spread=True,
+        kernels=["k_step_delay", "k_step_delay1_stats"])
+    run(n, 1000, 1024, 1, 1, 4, 0.0, seed=n + 1, spread=1e-3, k0=3, kernels=["k_step_delay", "k_step_delay1_stats"])
+
+
 def test_fused_local_iterations_between_communication_rounds():
     run(8, 2052, 2052, 2, 2, 7, 0.9, seed=3, spread=0.1, w_spread=True,
         kernels=["k_step_delay", "k_step_one_peer_stats", "k_step_delay2_stats"])
-    run(16, 1024, 1024, 1, 3, 7, 0.9, seed=4, spread=0.1, kernels=["k_step_delay", "k_step_one_peer_stats"])
+    run(16, 1024, 1024, 1, 3, 7, 0.9, seed=4, spread=0.1,
+        kernels=["k_step_delay", "k_step_one_peer_stats", "k_step_delay1_stats"])
 
 
 def test_fused_custom_rows():
