@@ -270,8 +270,8 @@ int sgp_pregossip_stats(sgp_handle *h, const float *x, const float *w, const flo
  * messages per node (one or two out-peers; the very first iteration, which receives nothing, does
  * not qualify); otherwise the two kernels run one after the other.  The state written is identical to
  * sgp_step's; the statistics agree with sgp_consensus_stats to rounding (a different reference row
- * is subtracted before squaring).  The reduction of the fused kernel's partial sums runs on a stream
- * that the library owns, behind the step kernel.  SYNCHRONISES the stream.
+ * is subtracted before squaring).  The reduction of the fused kernel's partial sums follows the step
+ * kernel on the caller's stream.  SYNCHRONISES the stream.
  */
 int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,
                    float gamma, float momentum, int64_t k, sgp_stats *host_out,
@@ -284,6 +284,8 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
  * waiting (for that result only) if it is not there yet.  At most two results may be outstanding:
  * a third begin returns SGP_ERR_SEQUENCE, as does an end with nothing outstanding.  Typical loop:
  * begin(k); if (k > 0) end(result of k-1); ... ; end(last).  The GPU then never waits for the host.
+ * The reduction of a fused kernel's partial sums and the copy run on a stream that the library owns,
+ * behind the step kernel, so that the caller's stream carries the step kernels and nothing else.
  * All begin calls between two ends must use streams that are ordered with respect to each other.
  */
 int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,

@@ -566,6 +566,8 @@ int sgp_peer_schedule(const sgp_handle *h, int64_t k, int32_t *out_peers, int32_
 // table (G blocks) in the slot's table for a walk with this hop and cycle length.
 struct FusedStats {
     int slot = 0;   // in: result slot whose table and weight copy the fused kernel may use
+    bool in_order = false;   // in: the caller waits for the result right away: the reduction goes onto the
+                             // caller's stream behind the step kernel, no event and no second stream between
     int G = 0, hop = 0, len = 1;
 };
 
@@ -687,7 +689,7 @@ static int step_impl(sgp_handle *h, float *x, float *w, float *m, const float *g
     hipEvent_t fin = nullptr;
     if (use_fused) {
         partial = h->d_partial_f[fused->slot];
-        fin = h->ev_step[fused->slot];
+        fin = fused->in_order ? nullptr : h->ev_step[fused->slot];
         a.wop.publish = 1;
         a.wop.w_snap = h->d_w_snap[fused->slot];
         fused->G = (int)grid_for(cols4, kStatsStepBlock);
@@ -894,8 +896,10 @@ static int enqueue_stats(sgp_handle *h, const FusedStats *fused, const float *w,
     double *d_res = h->d_result + (size_t)slot * (8 + n);
     hipStream_t rs = st;
     if (fused) {
-        rs = h->side;
-        SGP_HIP_TRY(h, hipStreamWaitEvent(rs, h->ev_step[slot], 0));   // recorded by the step kernel's launch
+        if (!fused->in_order) {
+            rs = h->side;
+            SGP_HIP_TRY(h, hipStreamWaitEvent(rs, h->ev_step[slot], 0));   // recorded by the step kernel's launch
+        }
         const int B = std::min(kSlotSumBlocks, fused->G);
         hipLaunchKernelGGL(k_stats_reduce_slots, dim3(B), dim3(kSlotSumBlock), 0, rs, h->d_partial_f[slot], fused->G,
                            h->d_sums_f[slot], h->d_done + kStepCounters + slot, n, fused->hop, fused->len, h->d_w_snap[slot],
@@ -948,6 +952,7 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
 {
     if (!z_out || !host_out) return SGP_ERR_INVALID_ARG;
     FusedStats fused;
+    fused.in_order = true;
     int rc = step_impl(h, x, w, m, g, z_out, gamma, momentum, k, stream, &fused);
     if (rc != SGP_OK) return rc;
     if (fused.G > 0)
