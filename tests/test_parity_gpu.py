@@ -306,6 +306,16 @@ def test_exact_averaging_on_device():
 _ALLOC = None
 
 
+@pytest.fixture(scope="module", autouse=True)
+def _release_the_arena_after_this_module():
+    """The arena holds nearly all device memory: whatever runs after this module gets it back."""
+    yield
+    global _ALLOC
+    _ALLOC = None
+    if torch.cuda.is_available():
+        torch.cuda.empty_cache()
+
+
 def _bench_allocator():
     """The benchmark's region-aware allocator, set up once for the full-size tests."""
     global _ALLOC
