@@ -284,8 +284,9 @@ int sgp_step_stats(sgp_handle *h, float *x, float *w, float *m, const float *g, 
  * waiting (for that result only) if it is not there yet.  At most two results may be outstanding:
  * a third begin returns SGP_ERR_SEQUENCE, as does an end with nothing outstanding.  Typical loop:
  * begin(k); if (k > 0) end(result of k-1); ... ; end(last).  The GPU then never waits for the host.
- * The reduction of a fused kernel's partial sums and the copy run on a stream that the library owns,
- * behind the step kernel, so that the caller's stream carries the step kernels and nothing else.
+ * The reduction of a fused kernel's partial sums runs on a stream that the library owns, behind the
+ * step kernel (its last block writes the result into pinned host memory), so that the caller's
+ * stream carries the step kernels and nothing else.
  * All begin calls between two ends must use streams that are ordered with respect to each other.
  */
 int sgp_step_stats_begin(sgp_handle *h, float *x, float *w, float *m, const float *g, float *z_out,

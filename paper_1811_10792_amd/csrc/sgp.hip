@@ -100,8 +100,9 @@ struct sgp_handle {
     bool fused_ready;
     hipStream_t side;       // the reduction of the fused statistics runs here, beside the next step
     hipEvent_t ev_step[kResultSlots];   // step kernel of the slot finished (recorded on the caller's stream)
-    double *d_result;   // [kResultSlots][8 + n]: slot 0 for the synchronous calls, 1.. for begin/end
-    double *h_result;   // pinned mirror
+    double *h_result;   // [kResultSlots][8 + n], pinned host memory that the last statistics kernel writes
+                        // directly (no copy behind it): slot 0 for the synchronous calls, 1.. for begin/end
+    double *h_result_dev;   // the same memory as the device addresses it
     hipEvent_t ev_res[kResultSlots];    // result of the slot copied to the host
     bool ev_made;
     int pend_head, pend_count;   // ring of outstanding begin/end results (slots 1 + index)
@@ -218,9 +219,10 @@ int ensure_device(sgp_handle *h)
     }
     if (!h->d_partial) SGP_HIP_TRY(h, dev_malloc(&h->d_partial, (size_t)(n + 1) * h->G * sizeof(float)));
     if (!h->d_sums) SGP_HIP_TRY(h, dev_malloc(&h->d_sums, (size_t)(n + 1) * sizeof(double)));
-    if (!h->d_result) SGP_HIP_TRY(h, dev_malloc(&h->d_result, res_bytes));
-    if (!h->h_result)
-        SGP_HIP_TRY(h, hipHostMalloc(reinterpret_cast<void **>(&h->h_result), res_bytes, hipHostMallocDefault));
+    if (!h->h_result) {
+        SGP_HIP_TRY(h, hipHostMalloc(reinterpret_cast<void **>(&h->h_result), res_bytes, hipHostMallocMapped));
+        SGP_HIP_TRY(h, hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_result_dev), h->h_result, 0));
+    }
     if (h->delay) {
         size_t bytes = (size_t)n * (size_t)h->ld * sizeof(float);
         for (int b = 0; b < 2; ++b) {
@@ -290,7 +292,6 @@ void release_device(sgp_handle *h)
     if (h->d_done) (void)hipFree(h->d_done);
     if (h->d_partial) (void)hipFree(h->d_partial);
     if (h->d_sums) (void)hipFree(h->d_sums);
-    if (h->d_result) (void)hipFree(h->d_result);
     if (h->h_result) (void)hipHostFree(h->h_result);
     for (int b = 0; b < 2; ++b) {
         if (h->d_msg[b] && !h->msg_external) (void)hipFree(h->d_msg[b]);
@@ -881,8 +882,9 @@ int sgp_step_bf16(sgp_handle *h, float *x, float *w, void *m, const void *g16, v
     return SGP_OK;
 }
 
-// Enqueues the reduction of a partial table to the statistics and their copy into result slot
-// `slot` of the pinned host buffer, and records ev_res[slot] behind the copy.
+// Enqueues the reduction of a partial table to the statistics, which the last kernel writes straight
+// into result slot `slot` of the pinned host buffer (8 + n doubles: no copy engine, no further
+// call), and records ev_res[slot] behind it.
 // fused == NULL: the stand-alone kernels' table [(n+1)][G], reduced on the caller's stream.
 // Otherwise the fused step kernel's table of that slot, reduced on the library's own stream behind
 // an event, so that the caller's stream is free for the next iteration at once; the weights are then
@@ -893,7 +895,7 @@ static int enqueue_stats(sgp_handle *h, const FusedStats *fused, const float *w,
     const int n = h->n;
     int rc = ensure_result_events(h);
     if (rc != SGP_OK) return rc;
-    double *d_res = h->d_result + (size_t)slot * (8 + n);
+    double *d_res = h->h_result_dev + (size_t)slot * (8 + n);   // 8 + n doubles, written once, over the bus
     hipStream_t rs = st;
     if (fused) {
         if (!fused->in_order) {
@@ -909,8 +911,6 @@ static int enqueue_stats(sgp_handle *h, const FusedStats *fused, const float *w,
         hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, rs, h->d_sums, n, w, d_res);
     }
     SGP_HIP_TRY(h, hipGetLastError());
-    SGP_HIP_TRY(h, hipMemcpyAsync(h->h_result + (size_t)slot * (8 + n), d_res, (size_t)(8 + n) * sizeof(double),
-                                  hipMemcpyDeviceToHost, rs));
     SGP_HIP_TRY(h, hipEventRecord(h->ev_res[slot], rs));
     return SGP_OK;
 }
@@ -930,8 +930,8 @@ static void read_stats(const sgp_handle *h, int slot, sgp_stats *host_out, doubl
         for (int i = 0; i < n; ++i) per_node_dist_host[i] = r[8 + i];
 }
 
-// Reduces a partial table to the statistics (slot 0), copies them to the host and waits: for the
-// result and for everything enqueued on the caller's stream before it.
+// Reduces a partial table to the statistics (slot 0, in host memory) and waits: for the result and
+// for everything enqueued on the caller's stream before it.
 static int finish_stats(sgp_handle *h, const FusedStats *fused, const float *w, sgp_stats *host_out,
                         double *per_node_dist_host, hipStream_t st)
 {
