@@ -68,6 +68,29 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.sgp_destroy(h) == 0
 
 
+def test_every_translation_unit_is_built_and_every_declared_walk_variant_has_an_object():
+    """build.py compiles each .hip file of csrc/, and the walk with fused statistics once for every
+    variant whose launcher csrc/internal.h declares (a missing object would only show up as an
+    undefined symbol when the library is loaded)."""
+    import glob
+    from paper_1811_10792_amd import build
+    csrc = os.path.join(os.path.dirname(build.__file__), "csrc")
+    sources = {os.path.basename(f) for f in glob.glob(os.path.join(csrc, "*.hip"))}
+    assert {src for src, _, _ in build.UNITS} == sources
+    assert len({name for _, name, _ in build.UNITS}) == len(build.UNITS)          # distinct objects
+    declared = set()
+    for m in re.finditer(r"^SGP_DECLARE_WALK_STATS\((\w+), (\w+), (\w+)\)", open(os.path.join(csrc, "internal.h")).read(),
+                         re.M):
+        nest, cached, msg = m.groups()
+        declared.add((int(nest == "true"), int(cached == "true"), int(msg)))
+    built = set()
+    for src, _, defs in build.UNITS:
+        if src == "sgp_walk_stats.hip":
+            d = dict(x[2:].split("=") for x in defs)
+            built.add((int(d["SGP_WALK_NEST"]), int(d["SGP_WALK_CACHED"]), int(d["SGP_WALK_MSG"])))
+    assert built == declared and len(built) == 8
+
+
 def test_stream_pattern_argument_checks(lib):
     """All of these are refused before anything is launched (the addresses are never touched)."""
     vp = ctypes.c_void_p
