@@ -68,6 +68,16 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.sgp_destroy(h) == 0
 
 
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built HIP library nothing runs: no CPU path stands in for it."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libsgp_hip.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        sgp.SGP(4, 16)
+
+
 def test_every_translation_unit_is_built_and_every_declared_walk_variant_has_an_object():
     """build.py compiles each .hip file of csrc/, and the walk with fused statistics once for every
     variant whose launcher csrc/internal.h declares (a missing object would only show up as an
